@@ -1,0 +1,161 @@
+/*
+ * moe_layer.h -- C ABI of the MI355X (gfx950) MoE expert-layer library.
+ *
+ * The library computes, on one GPU, the MoE layer that the DALI paper's offloading framework
+ * schedules: the gate of Eq. 1, the per-expert token workload that drives its Greedy Assignment
+ * (Alg. 1) and Workload-Aware Cache Replacement (Alg. 2), the residual-based next-layer workload
+ * prediction, the expert FFNs of the experts an assignment vector G places on this GPU, and the
+ * weighted combine of Eq. 2.
+ *
+ * Conventions (all entry points):
+ *   - Pointers marked [device] are HIP device pointers, pointers marked [host] are host pointers.
+ *     The caller owns every buffer, including the workspace; the library allocates nothing, keeps
+ *     no pointer after a call returns and never synchronises the device.
+ *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and returns.  Outputs are valid once the stream reaches that point.
+ *   - "bf16" is bfloat16 stored as 16-bit words; all matrices are row-major and densely packed.
+ *   - Return value: MOE_OK (0) or a negative error code.  Arguments are validated on the host
+ *     before anything is launched; on an error nothing has been enqueued and no device memory has
+ *     been touched.  moe_strerror() names a code.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics; the
+ *     token permutation is stable).
+ *
+ * Shape limits: 1 <= k <= 8, k <= N <= 128, T >= 1, T*k < 2^31, d a multiple of 128 (<= 8192),
+ * I a multiple of 32.
+ */
+#ifndef MOE_LAYER_H
+#define MOE_LAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK            0
+#define MOE_EINVAL       -1   /* null pointer, size out of range, misaligned pointer */
+#define MOE_EUNSUPPORTED -2   /* a valid request this build has no kernel for */
+#define MOE_ELAUNCH      -3   /* the HIP runtime refused a launch (hipGetLastError) */
+#define MOE_EWORKSPACE   -4   /* workspace pointer not 256-byte aligned */
+
+#define MOE_MAX_EXPERTS 128
+#define MOE_MAX_TOPK      8
+
+/* how the k selected scores become combine weights */
+#define MOE_NORM_NONE   0     /* G(x)_i = softmax over all N experts at the selected expert (Eq. 1 as printed) */
+#define MOE_NORM_RENORM 1     /* the k selected scores divided by their sum (= softmax over the k logits) */
+
+/* which expert-FFN kernels to use */
+#define MOE_FFN_AUTO   0      /* skinny when T <= 16, tiled otherwise */
+#define MOE_FFN_TILED  1      /* LDS-tiled bf16 MFMA grouped GEMMs (prefill) */
+#define MOE_FFN_SKINNY 2      /* weight-streaming path for at most 16 rows per expert (decode); needs T <= 16 */
+
+typedef struct moe_shape {
+    int32_t T;         /* tokens in the batch */
+    int32_t d;         /* hidden size */
+    int32_t N;         /* routed experts in the layer */
+    int32_t k;         /* experts selected per token */
+    int32_t I;         /* expert FFN inner size */
+    int32_t ffn_path;  /* MOE_FFN_* */
+} moe_shape;
+
+const char *moe_strerror(int code);
+
+/* Bytes of device workspace that any call with this shape may use.  [host] pointers only. */
+int moe_workspace_bytes(const moe_shape *s, size_t *bytes);
+
+/*
+ * Gate, top-k, workload histogram and token permutation (Section "Mixture of Experts (MoE)", Eq. 1;
+ * the expert workload w_i of Section "Greedy Assignment Strategy").
+ *
+ *   logits[t,e] = sum_j h[t,j] * gate_w[e,j] (+ gate_bias[e]),  fp32 accumulation;
+ *   scores      = softmax(logits[t,:]) over the N experts;
+ *   topk_idx[t,0..k) = the k experts with the highest score, by descending score, equal scores by
+ *                      ascending expert index;
+ *   topk_w[t,s] = score of topk_idx[t,s]            (MOE_NORM_NONE)
+ *               = that score / sum of the k scores  (MOE_NORM_RENORM);
+ *   counts[e]   = number of (t,s) pairs with topk_idx[t,s] = e   (the expert workload);
+ *   offsets[e]  = counts[0] + ... + counts[e-1], offsets[N] = T*k;
+ *   perm[offsets[e] + j] = the j-th smallest r = t*k+s routed to expert e (stable grouping);
+ *   inv_perm[perm[p]] = p.
+ *
+ * h [T,d] bf16 [device]; gate_w [N,d] bf16 [device] (row e = column e of the paper's d x N matrix W_g);
+ * gate_bias [N] fp32 [device] or NULL; topk_idx [T,k] int32, topk_w [T,k] fp32, counts [N] int32,
+ * offsets [N+1] int32, perm [T*k] int32, inv_perm [T*k] int32: all [device] outputs.
+ * workspace [device], 256-byte aligned, >= moe_workspace_bytes().  s->I is not used.
+ */
+int moe_route(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+              int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+              int32_t *inv_perm, void *workspace, void *stream);
+
+/*
+ * Residual-based next-layer workload prediction (Section "Residual-Based Prefetching", its two
+ * equations and the sentence after them): the next layer's gate is applied to h + res_vec (res_vec
+ * shared by all tokens), the tokens routed to each predicted expert are counted, and the p experts
+ * with the highest predicted workload are listed.
+ *
+ *   pred_counts[e]   = number of (t,s) pairs whose predicted expert is e (s < k);
+ *   top_experts[0..p) = experts by descending pred_counts, equal counts by ascending index.
+ *
+ * The logits are evaluated as h.W + (res_vec.W + bias), which equals (h + res_vec).W + bias up to
+ * fp32 rounding; h + res_vec is never rounded to bf16.
+ * h [T,d] bf16, res_vec [d] fp32, next_gate_w [N,d] bf16, next_gate_bias [N] fp32 or NULL,
+ * pred_counts [N] int32 out, top_experts [p] int32 out (1 <= p <= N): all [device].
+ */
+int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec, const void *next_gate_w,
+                         const float *next_gate_bias, int p, int32_t *pred_counts, int32_t *top_experts,
+                         void *workspace, void *stream);
+
+/*
+ * Expert FFNs of the experts placed on this GPU (the experts with G_i = 1 in Section "Greedy
+ * Assignment Strategy"; "each activated expert calculates the corresponding output using x",
+ * Section "Mixture of Experts (MoE)").  For every expert e with expert_mask[e] != 0 and
+ * counts[e] > 0, and each of its rows p in [offsets[e], offsets[e+1]):
+ *
+ *   x = h[perm[p] / k, :],   y[p,:] = W2_e ( silu(W1_e x) * (W3_e x) ),  silu(g) = g / (1 + exp(-g)).
+ *
+ * bf16 inputs, fp32 accumulation; the inner activation is rounded to bf16 once before the second
+ * product.  Rows of experts that are masked off are not written.
+ * h [T,d] bf16; perm [T*k], offsets [N+1], counts [N] int32 as produced by moe_route (or
+ * moe_dense_route); w1, w3 [N,I,d] bf16; w2 [N,d,I] bf16; expert_mask [N] uint8 (NULL = all on);
+ * y [T*k,d] bf16 out, in permuted row order: all [device].
+ */
+int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
+                   const int32_t *counts, const void *w1, const void *w3, const void *w2,
+                   const uint8_t *expert_mask, void *y, void *workspace, void *stream);
+
+/*
+ * Weighted combine (Eq. 2, restricted to the experts with G_i = 1):
+ *
+ *   out[t,:] = sum_{s<k, expert_mask[topk_idx[t,s]] != 0} topk_w[t,s] * y[inv_perm[t*k+s], :]
+ *            + shared_scale[t] * sum_{m<n_shared} shared_y[m*T + t, :]
+ *
+ * fp32 sum, rounded once to bf16.  The weights are not renormalised over the masked-on subset, so
+ * the outputs of complementary masks add up to the whole layer (mutual-exclusion constraint on C, G).
+ * y [T*k,d] bf16; topk_idx [T,k]; topk_w [T,k]; inv_perm [T*k]; expert_mask [N] uint8 or NULL;
+ * shared_y [n_shared*T, d] bf16 or NULL (expert-major, as moe_expert_ffn writes it under
+ * moe_dense_route); shared_scale [T] fp32 or NULL (= 1); out [T,d] bf16: all [device].  s->I unused.
+ */
+int moe_combine(const moe_shape *s, const void *y, const int32_t *topk_idx, const float *topk_w,
+                const int32_t *inv_perm, const uint8_t *expert_mask, const void *shared_y, int n_shared,
+                const float *shared_scale, void *out, void *stream);
+
+/*
+ * Routing tables of always-on shared experts (the "shared experts" column of the model table in
+ * Section "Experimental Setup"): every token goes to each of the s->N (= s->k) shared experts, so
+ * counts[e] = T, offsets[e] = e*T, perm[e*T + t] = t*k + e.  Lets moe_expert_ffn run them as a
+ * dense layer.  Requires s->k == s->N.  All pointers [device] outputs.
+ */
+int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32_t *perm, void *stream);
+
+/*
+ * Per-token scale of a sigmoid-gated shared expert: scale[t] = 1 / (1 + exp(-(h[t,:] . w_sg))).
+ * h [T,d] bf16, w_sg [d] bf16, scale [T] fp32 out: all [device].  Uses s->T and s->d only.
+ */
+int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *scale, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_LAYER_H */

@@ -1,0 +1,151 @@
+"""Thin ctypes binding of libmoe_mi355x.so: the same entry points as include/moe_layer.h, taking torch
+device tensors.  Argument marshalling only -- every step of the layer runs in the library's HIP kernels.
+There is no fallback: a missing library or a non-zero return code raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+from .build import LIB
+
+FFN_AUTO, FFN_TILED, FFN_SKINNY = 0, 1, 2
+NORM_NONE, NORM_RENORM = 0, 1
+
+EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
+           "moe_combine", "moe_dense_route", "moe_shared_gate"]
+
+
+class MoeShape(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("N", C.c_int32), ("k", C.c_int32), ("I", C.c_int32),
+                ("ffn_path", C.c_int32)]
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            raise MoeError(f"{LIB} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        _lib = C.CDLL(LIB)
+        _lib.moe_strerror.restype = C.c_char_p
+        _lib.moe_strerror.argtypes = [C.c_int]
+        for name in EXPORTS[1:]:
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MoeError(f"{what} failed: {load_library().moe_strerror(rc).decode()} (code {rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda or not t.is_contiguous():
+        raise MoeError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise MoeError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def shape(T: int, d: int, N: int, k: int, I: int, ffn_path: int = FFN_AUTO) -> MoeShape:
+    return MoeShape(T, d, N, k, I, ffn_path)
+
+
+def workspace_bytes(s: MoeShape) -> int:
+    n = C.c_size_t(0)
+    _check(load_library().moe_workspace_bytes(C.byref(s), C.byref(n)), "moe_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_workspace(s: MoeShape, device="cuda") -> torch.Tensor:
+    return torch.empty(workspace_bytes(s) + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_ptr(ws: torch.Tensor):
+    p = ws.data_ptr()
+    return C.c_void_p((p + 255) & ~255)
+
+
+@dataclass
+class Routing:
+    topk_idx: torch.Tensor   # [T,k] int32
+    topk_w: torch.Tensor     # [T,k] float32
+    counts: torch.Tensor     # [N] int32
+    offsets: torch.Tensor    # [N+1] int32
+    perm: torch.Tensor       # [T*k] int32
+    inv_perm: torch.Tensor   # [T*k] int32
+
+
+def alloc_routing(s: MoeShape, device="cuda") -> Routing:
+    R = s.T * s.k
+    i32 = dict(dtype=torch.int32, device=device)
+    return Routing(torch.empty((s.T, s.k), **i32), torch.empty((s.T, s.k), dtype=torch.float32, device=device),
+                   torch.empty(s.N, **i32), torch.empty(s.N + 1, **i32), torch.empty(R, **i32), torch.empty(R, **i32))
+
+
+def moe_route(s: MoeShape, h, gate_w, gate_bias, norm_mode: int, out: Routing, ws: torch.Tensor) -> Routing:
+    rc = load_library().moe_route(C.byref(s), _ptr(h, torch.bfloat16), _ptr(gate_w, torch.bfloat16),
+                                  _ptr(gate_bias, torch.float32), C.c_int(norm_mode), _ptr(out.topk_idx, torch.int32),
+                                  _ptr(out.topk_w, torch.float32), _ptr(out.counts, torch.int32),
+                                  _ptr(out.offsets, torch.int32), _ptr(out.perm, torch.int32),
+                                  _ptr(out.inv_perm, torch.int32), _ws_ptr(ws), _stream())
+    _check(rc, "moe_route")
+    return out
+
+
+def moe_predict_workload(s: MoeShape, h, res_vec, next_gate_w, next_gate_bias, p: int, pred_counts, top_experts,
+                         ws: torch.Tensor):
+    rc = load_library().moe_predict_workload(C.byref(s), _ptr(h, torch.bfloat16), _ptr(res_vec, torch.float32),
+                                             _ptr(next_gate_w, torch.bfloat16), _ptr(next_gate_bias, torch.float32),
+                                             C.c_int(p), _ptr(pred_counts, torch.int32), _ptr(top_experts, torch.int32),
+                                             _ws_ptr(ws), _stream())
+    _check(rc, "moe_predict_workload")
+    return pred_counts, top_experts
+
+
+def moe_expert_ffn(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, ws: torch.Tensor):
+    rc = load_library().moe_expert_ffn(C.byref(s), _ptr(h, torch.bfloat16), _ptr(perm, torch.int32),
+                                       _ptr(offsets, torch.int32), _ptr(counts, torch.int32), _ptr(w1, torch.bfloat16),
+                                       _ptr(w3, torch.bfloat16), _ptr(w2, torch.bfloat16), _ptr(expert_mask, torch.uint8),
+                                       _ptr(y, torch.bfloat16), _ws_ptr(ws), _stream())
+    _check(rc, "moe_expert_ffn")
+    return y
+
+
+def moe_combine(s: MoeShape, y, topk_idx, topk_w, inv_perm, expert_mask, shared_y, n_shared: int, shared_scale, out):
+    rc = load_library().moe_combine(C.byref(s), _ptr(y, torch.bfloat16), _ptr(topk_idx, torch.int32),
+                                    _ptr(topk_w, torch.float32), _ptr(inv_perm, torch.int32),
+                                    _ptr(expert_mask, torch.uint8), _ptr(shared_y, torch.bfloat16), C.c_int(n_shared),
+                                    _ptr(shared_scale, torch.float32), _ptr(out, torch.bfloat16), _stream())
+    _check(rc, "moe_combine")
+    return out
+
+
+def moe_dense_route(s: MoeShape, counts, offsets, perm):
+    rc = load_library().moe_dense_route(C.byref(s), _ptr(counts, torch.int32), _ptr(offsets, torch.int32),
+                                        _ptr(perm, torch.int32), _stream())
+    _check(rc, "moe_dense_route")
+
+
+def moe_shared_gate(s: MoeShape, h, w_sg, scale):
+    rc = load_library().moe_shared_gate(C.byref(s), _ptr(h, torch.bfloat16), _ptr(w_sg, torch.bfloat16),
+                                        _ptr(scale, torch.float32), _stream())
+    _check(rc, "moe_shared_gate")
+    return scale

@@ -1,0 +1,128 @@
+// extern "C" boundary of the library: argument validation on the host, then the kernel launchers.
+#include "moe_common.h"
+
+int moe_route_impl(const moe_shape *, const void *, const void *, const float *, int, int32_t *, float *, int32_t *,
+                   int32_t *, int32_t *, int32_t *, hipStream_t);
+int moe_predict_impl(const moe_shape *, const void *, const float *, const void *, const float *, int, int32_t *,
+                     int32_t *, void *, hipStream_t);
+int moe_dense_route_impl(const moe_shape *, int32_t *, int32_t *, int32_t *, hipStream_t);
+int moe_shared_gate_impl(const moe_shape *, const void *, const void *, float *, hipStream_t);
+int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
+                       const void *, const void *, const uint8_t *, void *, void *, hipStream_t);
+int moe_ffn_skinny_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
+                        const void *, const void *, const uint8_t *, void *, void *, hipStream_t);
+int moe_combine_impl(const moe_shape *, const void *, const int32_t *, const float *, const int32_t *, const uint8_t *,
+                     const void *, int, const float *, void *, hipStream_t);
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// sizes every entry point relies on
+static int check_shape(const moe_shape *s, bool need_I)
+{
+    if (s == nullptr) return MOE_EINVAL;
+    if (s->T < 1 || s->N < 1 || s->N > MOE_MAX_EXPERTS || s->k < 1 || s->k > MOE_MAX_TOPK || s->k > s->N) return MOE_EINVAL;
+    if ((long long)s->T * s->k >= (1ll << 31)) return MOE_EINVAL;
+    if (s->d < 128 || s->d > 8192 || s->d % 128 != 0) return MOE_EINVAL;
+    if (need_I && (s->I < 32 || s->I % 32 != 0)) return MOE_EINVAL;
+    return MOE_OK;
+}
+
+extern "C" {
+
+const char *moe_strerror(int code)
+{
+    switch (code) {
+    case MOE_OK: return "ok";
+    case MOE_EINVAL: return "invalid argument (null or misaligned pointer, or a size out of range)";
+    case MOE_EUNSUPPORTED: return "request not supported by this build (shape outside the chosen FFN path)";
+    case MOE_ELAUNCH: return "HIP kernel launch failed";
+    case MOE_EWORKSPACE: return "workspace pointer must be 256-byte aligned";
+    default: return "unknown error code";
+    }
+}
+
+int moe_workspace_bytes(const moe_shape *s, size_t *bytes)
+{
+    if (bytes == nullptr) return MOE_EINVAL;
+    int rc = check_shape(s, true);
+    if (rc != MOE_OK) return rc;
+    *bytes = moe_ws(s).total;
+    return MOE_OK;
+}
+
+int moe_route(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+              int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+              void *workspace, void *stream)
+{
+    int rc = check_shape(s, false);
+    if (rc != MOE_OK) return rc;
+    if (!h || !gate_w || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    if (!aligned16(h) || !aligned16(gate_w)) return MOE_EINVAL;
+    if (norm_mode != MOE_NORM_NONE && norm_mode != MOE_NORM_RENORM) return MOE_EINVAL;
+    (void)workspace;
+    return moe_route_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm,
+                          (hipStream_t)stream);
+}
+
+int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec, const void *next_gate_w,
+                         const float *next_gate_bias, int p, int32_t *pred_counts, int32_t *top_experts, void *workspace,
+                         void *stream)
+{
+    int rc = check_shape(s, true);
+    if (rc != MOE_OK) return rc;
+    if (!h || !res_vec || !next_gate_w || !pred_counts || !top_experts || !workspace) return MOE_EINVAL;
+    if (!aligned16(h) || !aligned16(next_gate_w)) return MOE_EINVAL;
+    if (p < 1 || p > s->N) return MOE_EINVAL;
+    if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    return moe_predict_impl(s, h, res_vec, next_gate_w, next_gate_bias, p, pred_counts, top_experts, workspace,
+                            (hipStream_t)stream);
+}
+
+int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets, const int32_t *counts,
+                   const void *w1, const void *w3, const void *w2, const uint8_t *expert_mask, void *y, void *workspace,
+                   void *stream)
+{
+    int rc = check_shape(s, true);
+    if (rc != MOE_OK) return rc;
+    if (!h || !perm || !offsets || !counts || !w1 || !w3 || !w2 || !y || !workspace) return MOE_EINVAL;
+    if (!aligned16(h) || !aligned16(w1) || !aligned16(w3) || !aligned16(w2) || !aligned16(y)) return MOE_EINVAL;
+    if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    int path = s->ffn_path;
+    if (path == MOE_FFN_AUTO) path = s->T <= MOE_SKINNY_MAX_T ? MOE_FFN_SKINNY : MOE_FFN_TILED;
+    if (path == MOE_FFN_SKINNY)
+        return moe_ffn_skinny_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, (hipStream_t)stream);
+    if (path == MOE_FFN_TILED)
+        return moe_ffn_tiled_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, (hipStream_t)stream);
+    return MOE_EINVAL;
+}
+
+int moe_combine(const moe_shape *s, const void *y, const int32_t *topk_idx, const float *topk_w, const int32_t *inv_perm,
+                const uint8_t *expert_mask, const void *shared_y, int n_shared, const float *shared_scale, void *out,
+                void *stream)
+{
+    int rc = check_shape(s, false);
+    if (rc != MOE_OK) return rc;
+    if (!y || !topk_idx || !topk_w || !inv_perm || !out) return MOE_EINVAL;
+    if (!aligned16(y) || !aligned16(out) || (shared_y && !aligned16(shared_y))) return MOE_EINVAL;
+    if (n_shared < 0 || (shared_y && n_shared < 1)) return MOE_EINVAL;
+    return moe_combine_impl(s, y, topk_idx, topk_w, inv_perm, expert_mask, shared_y, n_shared, shared_scale, out,
+                            (hipStream_t)stream);
+}
+
+int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32_t *perm, void *stream)
+{
+    int rc = check_shape(s, false);
+    if (rc != MOE_OK) return rc;
+    if (s->k != s->N) return MOE_EINVAL;
+    if (!counts || !offsets || !perm) return MOE_EINVAL;
+    return moe_dense_route_impl(s, counts, offsets, perm, (hipStream_t)stream);
+}
+
+int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *scale, void *stream)
+{
+    if (s == nullptr || s->T < 1 || s->d < 128 || s->d > 8192 || s->d % 128 != 0) return MOE_EINVAL;
+    if (!h || !w_sg || !scale || !aligned16(h) || !aligned16(w_sg)) return MOE_EINVAL;
+    return moe_shared_gate_impl(s, h, w_sg, scale, (hipStream_t)stream);
+}
+
+}   // extern "C"

@@ -1,0 +1,100 @@
+// Shared device helpers of the gfx950 MoE-layer kernels: bf16 packing, MFMA fragment types,
+// 64-lane wavefront reductions.  Internal to the library; the public boundary is include/moe_layer.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_layer.h"
+
+#define MOE_WAVE 64
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;   // one MFMA A/B fragment (8 bf16 along K)
+typedef __attribute__((ext_vector_type(4))) float f32x4;     // 16x16 accumulator fragment
+typedef __attribute__((ext_vector_type(16))) float f32x16;   // 32x32 accumulator fragment
+
+// Lane layouts of the two CDNA4 bf16 MFMA shapes used here (l = lane id):
+//   16x16x32: A[i][k] from lane l: i = l%16, k = 8*(l/16)+0..7; B[k][j]: j = l%16, same k;
+//             D[i][j]: lane l holds i = 4*(l/16)+r (r=0..3), j = l%16.
+//   32x32x16: A[i][k]: i = l%32, k = 8*(l/32)+0..7; B[k][j]: j = l%32, same k;
+//             D[i][j]: lane l holds i = 8*b + 4*(l/32) + r (b=0..3, r=0..3, element 4*b+r), j = l%32.
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // 16 bytes = 8 bf16, as loaded
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ bf16x8 as_frag(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// float -> bf16 bits, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, MOE_WAVE);
+    return v;
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+#define MOE_CHECK_LAUNCH()                       \
+    do {                                         \
+        if (hipGetLastError() != hipSuccess)     \
+            return MOE_ELAUNCH;                  \
+    } while (0)
+
+static inline size_t moe_align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- workspace layout (one per shape; every entry point carves what it needs from offset 0) ----
+struct moe_ws_layout {
+    size_t act;        // [T*k, I] bf16 inner activations
+    size_t partial;    // [nsplit, T*k, d] fp32 split-K partial sums of the skinny down projection
+    size_t sched;      // tile schedule of the tiled path
+    size_t route;      // scratch of moe_predict_workload: folded bias [N], idx [T*k], w [T*k]
+    size_t total;
+};
+
+#define MOE_SKINNY_MAX_T 16
+#define MOE_SKINNY_WAVES 4          // waves per block on the skinny path
+#define MOE_SKINNY_MAX_STEPS 32     // 32-wide K steps a wave may hold in registers (K <= 1024 per wave)
+#define MOE_TILE_M 128              // token rows per tile on the tiled path
+
+static inline int moe_skinny_nsplit(int K)
+{
+    int per_block = MOE_SKINNY_WAVES * MOE_SKINNY_MAX_STEPS * 32;
+    return (K + per_block - 1) / per_block;
+}
+
+static inline moe_ws_layout moe_ws(const moe_shape *s)
+{
+    moe_ws_layout L;
+    size_t R = (size_t)s->T * s->k;
+    size_t off = 0;
+    L.act = off;
+    off += moe_align256(R * (size_t)s->I * 2);
+    L.partial = off;
+    size_t Rs = R < (size_t)MOE_SKINNY_MAX_T * MOE_MAX_TOPK ? R : (size_t)MOE_SKINNY_MAX_T * MOE_MAX_TOPK;
+    off += moe_align256((size_t)moe_skinny_nsplit(s->I) * Rs * s->d * 4);
+    L.sched = off;
+    off += moe_align256(((size_t)R / MOE_TILE_M + MOE_MAX_EXPERTS + 8) * 16);
+    L.route = off;
+    off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4);
+    L.total = off;
+    return L;
+}

@@ -1,0 +1,320 @@
+// Gate, top-k, workload histogram, token permutation and next-layer workload prediction for gfx950.
+//
+// moe_route (Eq. 1 and the expert workload of Section "Greedy Assignment Strategy"):
+//   gate_topk_kernel      16 tokens per block; logits by bf16 MFMA 16x16x32 straight from global memory
+//                         (K split over the 4 waves, reduced through LDS), then softmax and top-k per token
+//                         inside one wavefront with xor-shuffle arg-max rounds.
+//   hist_scan_perm_kernel one block per expert: LDS-staged histogram of all selections (LDS atomics),
+//                         exclusive scan, and a ballot-based stable compaction of that expert's rows.
+// moe_predict_workload (Section "Residual-Based Prefetching"):
+//   fold_residual_kernel  bias'[e] = bias[e] + res_vec . W[e]   so that  (h + res_vec) . W + bias = h . W + bias'
+//   gate_topk_kernel      on the next layer's gate with bias'
+//   hist_top_kernel       histogram of the predicted experts and the p largest workloads.
+#include "moe_common.h"
+
+#define ROUTE_TOKENS 16      // tokens per block of gate_topk_kernel
+#define ROUTE_THREADS 256
+
+// ---------------------------------------------------------------------------------------------------
+template <int NT>   // NT = ceil(N / 16) expert tiles
+__global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
+    int T, int d, int N, int k, const uint16_t *__restrict__ h, const uint16_t *__restrict__ gate_w,
+    const float *__restrict__ bias, int norm_mode, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w)
+{
+    constexpr int NP = NT * 16;                       // padded expert count
+    __shared__ float part[4][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
+    __shared__ float lg[ROUTE_TOKENS][NP + 1];        // reduced logits (+bias)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * ROUTE_TOKENS;
+    const int i = lane & 15, g = lane >> 4;
+
+    // ---- logits: D[token][expert] += A[token][k] * B[k][expert], 32 k per MFMA -------------------
+    int tr = t0 + i;
+    if (tr >= T) tr = T - 1;
+    const uint16_t *hp = h + (size_t)tr * d + g * 8;
+    const uint16_t *wp[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int er = nt * 16 + i;
+        if (er >= N) er = N - 1;
+        wp[nt] = gate_w + (size_t)er * d + g * 8;
+    }
+    f32x4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = d >> 5;
+    for (int s = wave; s < nsteps; s += 4) {
+        bf16x8 a = as_frag(*reinterpret_cast<const uint4 *>(hp + s * 32));
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            bf16x8 b = as_frag(*reinterpret_cast<const uint4 *>(wp[nt] + s * 32));
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            part[wave][4 * g + r][nt * 16 + i] = acc[nt][r];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < ROUTE_TOKENS * NP; idx += ROUTE_THREADS) {
+        int tt = idx / NP, e = idx % NP;
+        float v = (part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e]);
+        if (bias != nullptr && e < N) v += bias[e];
+        lg[tt][e] = v;
+    }
+    __syncthreads();
+
+    // ---- softmax + top-k: one wave per token, lane l owns experts l and l+64 ---------------------
+    for (int q = 0; q < ROUTE_TOKENS / 4; ++q) {
+        const int tt = wave * (ROUTE_TOKENS / 4) + q;
+        const int t = t0 + tt;
+        if (t >= T) break;                                   // uniform per wave
+        const float NEG = -__builtin_huge_valf();
+        float v0 = lane < N ? lg[tt][lane] : NEG;
+        float v1 = (NT > 4 && lane + 64 < N) ? lg[tt][lane + 64] : NEG;
+        float m = fmaxf(v0, v1);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, MOE_WAVE));
+        float p0 = lane < N ? expf(v0 - m) : 0.f;
+        float p1 = (NT > 4 && lane + 64 < N) ? expf(v1 - m) : 0.f;
+        const float den = wave_sum(p0 + p1);
+
+        int my_idx = 0;
+        float my_p = 0.f;
+        for (int s = 0; s < k; ++s) {
+            float bv;
+            int bi;
+            if (v0 >= v1) { bv = v0; bi = lane; } else { bv = v1; bi = lane + 64; }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                float ov = __shfl_xor(bv, o, MOE_WAVE);
+                int oi = __shfl_xor(bi, o, MOE_WAVE);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (bi == lane) v0 = NEG;
+            if (bi == lane + 64) v1 = NEG;
+            if (lane == s) { my_idx = bi < N ? bi : N - 1; my_p = expf(bv - m) / den; }   // (NaN logits cannot index out of range)
+        }
+        float sel = wave_sum(lane < k ? my_p : 0.f);
+        if (lane < k) {
+            topk_idx[(size_t)t * k + lane] = my_idx;
+            topk_w[(size_t)t * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// One block per expert.  Every block histograms all R selections in LDS (cheap, and it spares a global
+// zero-fill and cross-block atomics), scans the N counts, and then places the rows of its own expert in
+// ascending r, so the permutation is stable and the same on every run.
+__global__ __launch_bounds__(256) void hist_scan_perm_kernel(
+    int R, int N, const int32_t *__restrict__ topk_idx, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm)
+{
+    __shared__ int hist[MOE_MAX_EXPERTS];
+    __shared__ int wave_tot[4];
+    __shared__ int my_off;
+    const int e = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    if (threadIdx.x < MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int r = threadIdx.x; r < R; r += 256) atomicAdd(&hist[topk_idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int j = 0; j < N; ++j) {
+            int c = hist[j];
+            if (j == e) my_off = run;
+            if (e == 0) { counts[j] = c; offsets[j] = run; }
+            run += c;
+        }
+        if (e == 0) offsets[N] = run;
+    }
+    __syncthreads();
+    int base = my_off;                                      // running output position, uniform
+    for (int c0 = 0; c0 < R; c0 += 1024) {
+        int r[4];
+        bool hit[4];
+        unsigned long long bal[4];
+        int tot = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            r[j] = c0 + wave * 256 + j * 64 + lane;
+            hit[j] = r[j] < R && topk_idx[r[j]] == e;
+            bal[j] = __ballot(hit[j]);
+            tot += __popcll(bal[j]);
+        }
+        if (lane == 0) wave_tot[wave] = tot;
+        __syncthreads();
+        int pos = base;
+        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+        const int chunk_tot = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        const unsigned long long lower = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (hit[j]) {
+                int p = pos + __popcll(bal[j] & lower);
+                perm[p] = r[j];
+                inv_perm[r[j]] = p;
+            }
+            pos += __popcll(bal[j]);
+        }
+        base += chunk_tot;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void fold_residual_kernel(int d, const float *__restrict__ res_vec,
+                                                           const uint16_t *__restrict__ gate_w,
+                                                           const float *__restrict__ bias, float *__restrict__ bias_out)
+{
+    const int e = blockIdx.x, lane = threadIdx.x;
+    const uint16_t *w = gate_w + (size_t)e * d;
+    float acc = 0.f;
+    for (int j = lane * 2; j < d; j += 128) {
+        uint32_t pr = *reinterpret_cast<const uint32_t *>(w + j);
+        acc = fmaf(res_vec[j], bf16_lo(pr), acc);
+        acc = fmaf(res_vec[j + 1], bf16_hi(pr), acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) bias_out[e] = acc + (bias != nullptr ? bias[e] : 0.f);
+}
+
+__global__ __launch_bounds__(256) void hist_top_kernel(int R, int N, int p, const int32_t *__restrict__ idx,
+                                                       int32_t *__restrict__ pred_counts, int32_t *__restrict__ top)
+{
+    __shared__ int hist[MOE_MAX_EXPERTS];
+    if (threadIdx.x < MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int r = threadIdx.x; r < R; r += 256) atomicAdd(&hist[idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
+    __syncthreads();
+    if (threadIdx.x < N) pred_counts[threadIdx.x] = hist[threadIdx.x];
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        int c0 = lane < N ? hist[lane] : -1;
+        int c1 = lane + 64 < N ? hist[lane + 64] : -1;
+        for (int s = 0; s < p; ++s) {
+            int bc, bi;
+            if (c0 >= c1) { bc = c0; bi = lane; } else { bc = c1; bi = lane + 64; }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                int oc = __shfl_xor(bc, o, MOE_WAVE);
+                int oi = __shfl_xor(bi, o, MOE_WAVE);
+                if (oc > bc || (oc == bc && oi < bi)) { bc = oc; bi = oi; }
+            }
+            if (bi == lane) c0 = -1;
+            if (bi == lane + 64) c1 = -1;
+            if (lane == 0) top[s] = bi;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+__global__ void dense_route_kernel(int T, int S, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+                                   int32_t *__restrict__ perm)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < T * S) {
+        int e = p / T, t = p - e * T;
+        perm[p] = t * S + e;
+    }
+    if (p < S) { counts[p] = T; offsets[p] = p * T; }
+    if (p == 0) offsets[S] = S * T;
+}
+
+__global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const uint16_t *__restrict__ h,
+                                                          const uint16_t *__restrict__ w_sg, float *__restrict__ scale)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint16_t *x = h + (size_t)t * d;
+    float acc = 0.f;
+    for (int j = lane * 8; j < d; j += 512) {
+        uint4 a = *reinterpret_cast<const uint4 *>(x + j);
+        uint4 b = *reinterpret_cast<const uint4 *>(w_sg + j);
+        acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+        acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+        acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+        acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) scale[t] = 1.0f / (1.0f + expf(-acc));
+}
+
+// ---------------------------------------------------------------------------------------------------
+// host side
+static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_w, const float *bias, int norm_mode,
+                            int32_t *topk_idx, float *topk_w, hipStream_t st)
+{
+    const int NT = (s->N + 15) / 16;
+    dim3 grid((s->T + ROUTE_TOKENS - 1) / ROUTE_TOKENS), block(ROUTE_THREADS);
+    const uint16_t *hp = (const uint16_t *)h, *wp = (const uint16_t *)gate_w;
+#define GT(n)                                                                                                       \
+    case n:                                                                                                         \
+        hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode, \
+                           topk_idx, topk_w);                                                                       \
+        break;
+    switch (NT) {
+        GT(1) GT(2) GT(3) GT(4) GT(5) GT(6) GT(7) GT(8)
+    default:
+        return MOE_EUNSUPPORTED;
+    }
+#undef GT
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+int moe_route_impl(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                   int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                   int32_t *inv_perm, hipStream_t st)
+{
+    int rc = launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(hist_scan_perm_kernel, dim3(s->N), dim3(256), 0, st, s->T * s->k, s->N, topk_idx, counts,
+                       offsets, perm, inv_perm);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+int moe_predict_impl(const moe_shape *s, const void *h, const float *res_vec, const void *next_gate_w,
+                     const float *next_gate_bias, int p, int32_t *pred_counts, int32_t *top_experts, void *workspace,
+                     hipStream_t st)
+{
+    moe_ws_layout L = moe_ws(s);
+    char *ws = (char *)workspace + L.route;
+    float *bias2 = (float *)ws;
+    size_t R = (size_t)s->T * s->k;
+    int32_t *idx = (int32_t *)(ws + moe_align256(MOE_MAX_EXPERTS * 4));
+    float *w = (float *)(ws + moe_align256(MOE_MAX_EXPERTS * 4) + moe_align256(R * 4));
+    hipLaunchKernelGGL(fold_residual_kernel, dim3(s->N), dim3(64), 0, st, s->d, res_vec, (const uint16_t *)next_gate_w,
+                       next_gate_bias, bias2);
+    MOE_CHECK_LAUNCH();
+    int rc = launch_gate_topk(s, h, next_gate_w, bias2, MOE_NORM_NONE, idx, w, st);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(hist_top_kernel, dim3(1), dim3(256), 0, st, (int)R, s->N, p, idx, pred_counts, top_experts);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+int moe_dense_route_impl(const moe_shape *s, int32_t *counts, int32_t *offsets, int32_t *perm, hipStream_t st)
+{
+    int n = s->T * s->N;
+    hipLaunchKernelGGL(dense_route_kernel, dim3((n + 255) / 256), dim3(256), 0, st, s->T, s->N, counts, offsets, perm);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+int moe_shared_gate_impl(const moe_shape *s, const void *h, const void *w_sg, float *scale, hipStream_t st)
+{
+    hipLaunchKernelGGL(shared_gate_kernel, dim3((s->T + 3) / 4), dim3(256), 0, st, s->T, s->d, (const uint16_t *)h,
+                       (const uint16_t *)w_sg, scale);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}

@@ -1,0 +1,99 @@
+"""Host-side checks of the C ABI: the built library loads, exports every function the header declares, and
+rejects bad arguments before anything is launched (so these calls are safe without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moe_layer.h")
+LIB = os.path.join(ROOT, "paper_2602_03495_amd", "libmoe_mi355x.so")
+
+MOE_OK, MOE_EINVAL, MOE_EUNSUPPORTED, MOE_ELAUNCH, MOE_EWORKSPACE = 0, -1, -2, -3, -4
+
+
+class Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("T", "d", "N", "k", "I", "ffn_path")]
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import __graft_entry__ as g
+        g.build()
+    return C.CDLL(LIB)
+
+
+def test_header_declares_the_four_named_calls():
+    names = declared_functions()
+    for n in ("moe_route", "moe_predict_workload", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
+              "moe_strerror", "moe_dense_route", "moe_shared_gate"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_symbols():
+    from paper_2602_03495_amd import binding
+    assert sorted(binding.EXPORTS) == declared_functions()
+    assert C.sizeof(binding.MoeShape) == 24
+
+
+def test_strerror(lib):
+    lib.moe_strerror.restype = C.c_char_p
+    assert lib.moe_strerror(0) == b"ok"
+    for code in (MOE_EINVAL, MOE_EUNSUPPORTED, MOE_ELAUNCH, MOE_EWORKSPACE, -99):
+        assert len(lib.moe_strerror(code)) > 0
+
+
+def test_workspace_bytes_and_shape_validation(lib):
+    n = C.c_size_t(0)
+    good = Shape(2048, 4096, 8, 2, 14336, 0)
+    assert lib.moe_workspace_bytes(C.byref(good), C.byref(n)) == MOE_OK
+    R = 2048 * 2
+    assert n.value >= R * 14336 * 2           # room for the inner activations
+    assert n.value < 2 * R * 14336 * 2
+    assert lib.moe_workspace_bytes(C.byref(good), None) == MOE_EINVAL
+    assert lib.moe_workspace_bytes(None, C.byref(n)) == MOE_EINVAL
+    for bad in (Shape(0, 4096, 8, 2, 14336, 0),      # no tokens
+                Shape(16, 4096, 8, 9, 14336, 0),     # k > N
+                Shape(16, 4096, 8, 0, 14336, 0),     # k < 1
+                Shape(16, 4096, 129, 2, 14336, 0),   # too many experts
+                Shape(16, 4096, 64, 9, 14336, 0),    # k above the supported maximum
+                Shape(16, 4100, 8, 2, 14336, 0),     # d not a multiple of 128
+                Shape(16, 16384, 8, 2, 14336, 0),    # d too large
+                Shape(16, 4096, 8, 2, 100, 0)):      # I not a multiple of 32
+        assert lib.moe_workspace_bytes(C.byref(bad), C.byref(n)) == MOE_EINVAL
+
+
+def test_entry_points_reject_null_and_misaligned_pointers_before_launching(lib):
+    s = Shape(16, 256, 8, 2, 512, 0)
+    p = C.c_void_p(0x1000)        # never dereferenced: validation fails first
+    z = C.c_void_p(0)
+    assert lib.moe_route(C.byref(s), z, p, z, 1, p, p, p, p, p, p, p, z) == MOE_EINVAL
+    assert lib.moe_route(C.byref(s), p, p, z, 7, p, p, p, p, p, p, p, z) == MOE_EINVAL          # bad norm mode
+    assert lib.moe_route(C.byref(s), C.c_void_p(0x1004), p, z, 1, p, p, p, p, p, p, p, z) == MOE_EINVAL
+    assert lib.moe_predict_workload(C.byref(s), p, p, p, z, 0, p, p, p, z) == MOE_EINVAL         # p < 1
+    assert lib.moe_predict_workload(C.byref(s), p, p, p, z, 9, p, p, p, z) == MOE_EINVAL         # p > N
+    assert lib.moe_predict_workload(C.byref(s), p, z, p, z, 2, p, p, p, z) == MOE_EINVAL         # no res_vec
+    assert lib.moe_predict_workload(C.byref(s), p, p, p, z, 2, p, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
+    assert lib.moe_expert_ffn(C.byref(s), p, p, p, p, p, p, z, z, p, p, z) == MOE_EINVAL          # no w2
+    assert lib.moe_expert_ffn(C.byref(s), p, p, p, p, p, p, p, z, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
+    bad_path = Shape(16, 256, 8, 2, 512, 5)
+    assert lib.moe_expert_ffn(C.byref(bad_path), p, p, p, p, p, p, p, z, p, p, z) == MOE_EINVAL
+    skinny_big = Shape(64, 256, 8, 2, 512, 2)     # the skinny path takes at most 16 tokens
+    assert lib.moe_expert_ffn(C.byref(skinny_big), p, p, p, p, p, p, p, z, p, p, z) == MOE_EUNSUPPORTED
+    assert lib.moe_combine(C.byref(s), p, p, p, p, z, z, 0, z, z, z) == MOE_EINVAL                # no out
+    assert lib.moe_combine(C.byref(s), p, p, p, p, z, p, 0, z, p, z) == MOE_EINVAL                # shared_y without count
+    assert lib.moe_dense_route(C.byref(s), p, p, p, z) == MOE_EINVAL                              # needs k == N
+    assert lib.moe_shared_gate(C.byref(s), p, z, p, z) == MOE_EINVAL

@@ -1,0 +1,242 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs, at sizes the oracle
+finishes in seconds (several tiles plus a ragged tail)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_03495_amd import workloads as wl
+from helpers import OUT_TOL, check_routing, make_host_layer, rel_err
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_03495_amd import binding, layer
+    binding.load_library()
+    return binding, layer
+
+
+def _upload(layer_mod, hl):
+    return layer_mod.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2, hl.shared)
+
+
+def _np(t):
+    return t.cpu().numpy()
+
+
+SMALL = {
+    "tiny": wl.CONFIGS["tiny"],
+    "mixtral_s": wl.scaled(wl.CONFIGS["mixtral"], d=512, I=1792),
+    "deepseek_s": wl.scaled(wl.CONFIGS["deepseek"], d=256, I=192, I_shared=192),
+    "qwen15_s": wl.scaled(wl.CONFIGS["qwen15"], d=256, I=192, I_shared=704),
+    "qwen3_s": wl.scaled(wl.CONFIGS["qwen3"], d=256, I=128),
+}
+
+
+# ------------------------------------------------------------------------------------------- moe_route
+@pytest.mark.parametrize("name,T", [("tiny", 64), ("tiny", 1), ("mixtral_s", 300), ("deepseek_s", 1000),
+                                    ("qwen15_s", 17), ("qwen15_s", 1100), ("qwen3_s", 16), ("qwen3_s", 777)])
+def test_route_matches_oracle(gpu, name, T):
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"route {name} T={T}", flush=True)
+    h = wl.hidden_states(cfg, T)
+    W, b = wl.gate_weights(cfg), wl.gate_bias(cfg)
+    lg, o_idx, o_w, o_counts = oracle.route(h, W, b, cfg.k, cfg.norm_mode)
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    ws = B.alloc_workspace(s)
+    r = B.alloc_routing(s)
+    B.moe_route(s, Lm.to_device_bf16(h), Lm.to_device_bf16(W), torch.from_numpy(b).cuda(), cfg.norm_mode, r, ws)
+    torch.cuda.synchronize()
+    check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
+                  _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
+
+
+def test_route_other_norm_mode_and_no_bias(gpu):
+    B, Lm = gpu
+    cfg = SMALL["deepseek_s"]
+    T = 130
+    h, W = wl.hidden_states(cfg, T, draw=3), wl.gate_weights(cfg)
+    for mode in (wl.NORM_NONE, wl.NORM_RENORM):
+        lg, o_idx, o_w, o_counts = oracle.route(h, W, None, cfg.k, mode)
+        s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+        r = B.alloc_routing(s)
+        B.moe_route(s, Lm.to_device_bf16(h), Lm.to_device_bf16(W), None, mode, r, B.alloc_workspace(s))
+        torch.cuda.synchronize()
+        check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
+                      _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
+        if mode == wl.NORM_RENORM:
+            assert np.allclose(_np(r.topk_w).sum(1), 1.0, atol=1e-5)
+
+
+def test_route_extreme_bias_sends_every_token_to_one_expert(gpu):
+    B, Lm = gpu
+    cfg = SMALL["qwen3_s"]
+    T = 200
+    h, W, b = wl.hidden_states(cfg, T), wl.gate_weights(cfg), wl.gate_bias(cfg).copy()
+    b[77] += 1e4
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    r = B.alloc_routing(s)
+    B.moe_route(s, Lm.to_device_bf16(h), Lm.to_device_bf16(W), torch.from_numpy(b).cuda(), cfg.norm_mode, r,
+                B.alloc_workspace(s))
+    torch.cuda.synchronize()
+    assert int(_np(r.counts)[77]) == T and np.all(_np(r.topk_idx)[:, 0] == 77)
+    assert np.all(np.isfinite(_np(r.topk_w)))
+
+
+# ------------------------------------------------------------------------------------------- expert FFN + combine
+def _run_layer(B, Lm, cfg, T, masks, ffn_path, draw=0):
+    hl = make_host_layer(cfg)
+    h = wl.hidden_states(cfg, T, draw=draw)
+    lg, o_idx, o_w, o_counts = oracle.route(h, hl.gate_w, hl.bias, cfg.k, cfg.norm_mode)
+    dw = _upload(Lm, hl)
+    L = Lm.MoeLayer(cfg, T, ffn_path)
+    hd = Lm.to_device_bf16(h)
+    for mask in masks:
+        md = None if mask is None else torch.from_numpy(mask).cuda()
+        L.y.zero_()
+        out = L.forward(hd, dw, md)
+        torch.cuda.synchronize()
+        r = L.routing
+        ex = check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
+                           _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
+        keep = np.nonzero(~ex)[0].astype(np.int32)
+        # expert rows, in the oracle's (token, slot) order
+        y_ref = oracle.expert_rows(h, o_idx, hl.w1, hl.w3, hl.w2, mask, tokens=keep)
+        y_gpu = wl.bf16_bits_to_f32(Lm.from_device_bf16(L.y))
+        g_idx, inv = _np(r.topk_idx), _np(r.inv_perm).reshape(T, cfg.k)
+        on = np.ones(cfg.N, bool) if mask is None else mask.astype(bool)
+        for n, t in enumerate(keep):
+            for s_o in range(cfg.k):
+                e = o_idx[t, s_o]
+                if not on[e]:
+                    continue
+                s_g = int(np.nonzero(g_idx[t] == e)[0][0])
+                err = rel_err(y_gpu[inv[t, s_g]], y_ref[n, s_o])
+                assert err <= OUT_TOL, (t, e, err)
+        # layer output
+        ref = oracle.layer(h, o_idx, o_w, hl.w1, hl.w3, hl.w2, mask, hl.shared, hl.shared_mode, tokens=keep)
+        got = wl.bf16_bits_to_f32(Lm.from_device_bf16(out))[keep]
+        if np.abs(ref).max() == 0:
+            assert np.all(got == 0)
+        else:
+            assert rel_err(got, ref) <= OUT_TOL, rel_err(got, ref)
+    return L
+
+
+@pytest.mark.parametrize("path", ["tiled", "skinny"])
+def test_tiny_layer_with_the_three_masks(gpu, path):
+    B, Lm = gpu
+    cfg = SMALL["tiny"]
+    T = 64 if path == "tiled" else 16
+    print(f"tiny layer {path}", flush=True)
+    masks = [wl.mask_lower(cfg.N, 4), np.ones(cfg.N, np.uint8), np.zeros(cfg.N, np.uint8), None]
+    _run_layer(B, Lm, cfg, T, masks, B.FFN_TILED if path == "tiled" else B.FFN_SKINNY)
+
+
+@pytest.mark.parametrize("name,T", [("mixtral_s", 300), ("deepseek_s", 333), ("qwen15_s", 257), ("qwen3_s", 190)])
+def test_scaled_layers_tiled_path(gpu, name, T):
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"tiled {name} T={T}", flush=True)
+    mask = wl.mask_random(cfg, (3 * cfg.N) // 4)
+    _run_layer(B, Lm, cfg, T, [mask], B.FFN_TILED)
+
+
+@pytest.mark.parametrize("name,T", [("mixtral_s", 1), ("mixtral_s", 16), ("deepseek_s", 16), ("qwen15_s", 1),
+                                    ("qwen3_s", 16), ("qwen3_s", 5)])
+def test_scaled_layers_skinny_path(gpu, name, T):
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"skinny {name} T={T}", flush=True)
+    mask = wl.mask_random(cfg, (3 * cfg.N) // 4)
+    _run_layer(B, Lm, cfg, T, [mask, None], B.FFN_AUTO)
+
+
+def test_skinny_split_k_down_projection(gpu):
+    # inner size above 4096 makes the down projection split K over blocks and finish in a second kernel
+    B, Lm = gpu
+    cfg = wl.scaled(wl.CONFIGS["mixtral"], d=256, I=4608)
+    _run_layer(B, Lm, cfg, 16, [wl.mask_random(cfg, 6)], B.FFN_SKINNY)
+
+
+def test_tiled_and_skinny_paths_agree_and_runs_are_deterministic(gpu):
+    B, Lm = gpu
+    cfg = SMALL["qwen3_s"]
+    T = 16
+    hl = make_host_layer(cfg)
+    dw = _upload(Lm, hl)
+    hd = Lm.to_device_bf16(wl.hidden_states(cfg, T))
+    outs = []
+    for path in (B.FFN_TILED, B.FFN_SKINNY, B.FFN_TILED, B.FFN_SKINNY):
+        L = Lm.MoeLayer(cfg, T, path)
+        outs.append(Lm.from_device_bf16(L.forward(hd, dw, None)).copy())
+    torch.cuda.synchronize()
+    assert np.array_equal(outs[0], outs[2]) and np.array_equal(outs[1], outs[3])
+    a, b = wl.bf16_bits_to_f32(outs[0]), wl.bf16_bits_to_f32(outs[1])
+    assert rel_err(a, b.astype(np.float64)) <= OUT_TOL
+
+
+def test_mask_additivity_on_gpu(gpu):
+    # outputs under a mask and under its complement add up to the all-on output (each expert on one side only)
+    B, Lm = gpu
+    cfg = SMALL["deepseek_s"]
+    T = 200
+    hl = make_host_layer(cfg)
+    dw = _upload(Lm, hl)
+    hd = Lm.to_device_bf16(wl.hidden_states(cfg, T))
+    L = Lm.MoeLayer(cfg, T, B.FFN_TILED)
+    m = wl.mask_random(cfg, cfg.N // 2)
+
+    def run(mask):
+        md = None if mask is None else torch.from_numpy(mask).cuda()
+        o = L.forward(hd, dw, md, with_shared=False)
+        return wl.bf16_bits_to_f32(Lm.from_device_bf16(o)).astype(np.float64)
+
+    full, a, c = run(None), run(m), run(1 - m)
+    assert rel_err(a + c, full) <= OUT_TOL
+    assert np.all(run(np.zeros(cfg.N, np.uint8)) == 0)
+
+
+# ------------------------------------------------------------------------------------------- prediction
+@pytest.mark.parametrize("name,T,p", [("tiny", 64, 2), ("qwen15_s", 500, 4), ("qwen3_s", 16, 8), ("deepseek_s", 1, 4)])
+def test_predict_workload(gpu, name, T, p):
+    B, Lm = gpu
+    cfg = SMALL[name]
+    h = wl.hidden_states(cfg, T)
+    W0, b0 = wl.gate_weights(cfg, 0), wl.gate_bias(cfg, 0)
+    W1, b1 = wl.gate_weights(cfg, 1), wl.gate_bias(cfg, 1)
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    ws = B.alloc_workspace(s)
+    hd = Lm.to_device_bf16(h)
+    pc = torch.empty(cfg.N, dtype=torch.int32, device="cuda")
+    top = torch.empty(p, dtype=torch.int32, device="cuda")
+
+    # zero residual and the layer's own gate: prediction == routing, bit for bit
+    r = B.alloc_routing(s)
+    B.moe_route(s, hd, Lm.to_device_bf16(W0), torch.from_numpy(b0).cuda(), cfg.norm_mode, r, ws)
+    B.moe_predict_workload(s, hd, torch.zeros(cfg.d, device="cuda"), Lm.to_device_bf16(W0), torch.from_numpy(b0).cuda(),
+                           p, pc, top, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(pc), _np(r.counts))
+    assert np.array_equal(_np(top), oracle.top_p(_np(r.counts), p))
+
+    # next layer's gate on h + res_vec
+    rv = wl.layer_drift(cfg)
+    lg, o_idx, o_cnt, o_top = oracle.predict_workload(h, rv, W1, b1, cfg.k, p)
+    B.moe_predict_workload(s, hd, torch.from_numpy(rv).cuda(), Lm.to_device_bf16(W1), torch.from_numpy(b1).cuda(), p, pc,
+                           top, ws)
+    torch.cuda.synchronize()
+    from helpers import exempt_tokens
+    nex = int(exempt_tokens(lg, cfg.k).sum())
+    g_cnt = _np(pc)
+    assert g_cnt.sum() == T * cfg.k
+    assert int(np.abs(g_cnt.astype(np.int64) - o_cnt).sum()) <= 2 * nex
+    assert np.array_equal(_np(top), oracle.top_p(g_cnt, p))
+    if nex == 0:
+        assert np.array_equal(_np(top), o_top)
