@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""MoE-layer throughput on one MI355X.
+
+A step is one pass of the whole path -- moe_route, moe_expert_ffn (masked), moe_combine -- over one batch of
+synthetic input that is already resident in HBM.  The headline workload is the Mixtral-8x7B-shaped layer
+(d=4096, 8 experts top-2, SwiGLU inner 14336, 6 of 8 experts on this GPU) at a prefill of 2048 tokens; the
+same layer at decode batches of 1 and 16 tokens is timed in the same run and reported under "decode".
+The dominant kernel (the gate/up projection of the expert FFN) is bracketed by HIP events in every timed
+step; its algorithmic flops (prefill) or bytes (decode) over its mean duration give the roofline fraction.
+The CPU oracle is timed beside it on a bounded token sample of the same batch.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15   # flop/s, MI355X dense bf16 matrix peak
+PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_steps(torch, B, L, hd, dw, mask_d, steps, warmup):
+    """Run warmup + steps passes; returns (wall seconds for the timed steps, mean seconds of the up-projection
+    stage, mean seconds of the whole FFN), with HIP events recorded on the stream the kernels run on."""
+    r, s = L.routing, L.shape
+
+    def one(ev=None):
+        L.route(hd, dw)
+        if ev is not None:
+            ev[0].record()
+        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_UP)
+        if ev is not None:
+            ev[1].record()
+        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_DOWN)
+        if ev is not None:
+            ev[2].record()
+        L.combine(mask_d)
+
+    for _ in range(warmup):
+        one()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    up = sum(e[0].elapsed_time(e[1]) for e in evs) / steps * 1e-3
+    ffn = sum(e[0].elapsed_time(e[2]) for e in evs) / steps * 1e-3
+    return wall, up, ffn
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--decode-steps", type=int, default=50)
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2602_03495_amd import binding as B
+    from paper_2602_03495_amd import layer as Lm
+    from paper_2602_03495_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.load_library()   # raises if the HIP library has not been built
+    torch.cuda.set_device(0)
+
+    cfg = wl.CONFIGS["mixtral"]
+    T = 2048
+    t0 = time.time()
+    W, b = wl.gate_weights(cfg), wl.gate_bias(cfg)
+    w1, w3, w2 = wl.expert_weights(cfg)
+    mask = wl.mask_random(cfg, 6)
+    log(f"[bench] generated {cfg.name} weights in {time.time() - t0:.1f}s; mask={mask.tolist()}")
+    dw = Lm.LayerWeights.upload(W, b, w1, w3, w2)
+    mask_d = torch.from_numpy(mask).cuda()
+    on = mask.astype(bool)
+
+    # ---- prefill ------------------------------------------------------------------------------------
+    h = wl.hidden_states(cfg, T)
+    hd = Lm.to_device_bf16(h)
+    L = Lm.MoeLayer(cfg, T)
+    wall, up, ffn = time_steps(torch, B, L, hd, dw, mask_d, args.steps, args.warmup)
+    counts = L.routing.counts.cpu().numpy()
+    rows_on = int(counts[on].sum())
+    up_flops = 4.0 * cfg.d * cfg.I * rows_on           # gate + up products of the masked-on rows
+    ffn_flops = 6.0 * cfg.d * cfg.I * rows_on
+    ms_per_step = wall / args.steps * 1e3
+    value = T / (wall / args.steps)
+    log(f"[bench] prefill T={T}: {ms_per_step:.3f} ms/step, up {up * 1e3:.3f} ms, ffn {ffn * 1e3:.3f} ms, "
+        f"counts={counts.tolist()}, rows_on={rows_on}")
+    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0> (gate/up projection + SwiGLU)",
+                "achieved": up_flops / up / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
+                "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": None,
+                "ffn_achieved": ffn_flops / ffn / 1e12, "ffn_frac": ffn_flops / ffn / PEAK_BF16_MFMA,
+                "flops_per_launch": up_flops, "avg_launch_ms": up * 1e3}
+
+    # ---- decode -------------------------------------------------------------------------------------
+    decode = []
+    if not args.no_decode:
+        for Td in (1, 16):
+            hdd = Lm.to_device_bf16(wl.hidden_states(cfg, Td, draw=10 + Td))
+            Ld = Lm.MoeLayer(cfg, Td)
+            wall_d, up_d, ffn_d = time_steps(torch, B, Ld, hdd, dw, mask_d, args.decode_steps, args.warmup)
+            c = Ld.routing.counts.cpu().numpy()
+            active = int(((c > 0) & on).sum())
+            up_bytes = 4.0 * cfg.d * cfg.I * active          # W1 and W3 of the touched, masked-on experts, bf16
+            ffn_bytes = 6.0 * cfg.d * cfg.I * active
+            decode.append({"T": Td, "value": Td / (wall_d / args.decode_steps), "unit": "tokens/s",
+                           "ms_per_step": wall_d / args.decode_steps * 1e3, "active_experts": active,
+                           "roofline": {"bound": "hbm", "kernel": "skinny_up_kernel", "achieved": up_bytes / up_d / 1e9 if active else 0.0,
+                                        "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": up_bytes / up_d / PEAK_HBM if active else 0.0,
+                                        "ffn_frac": ffn_bytes / ffn_d / PEAK_HBM if active else 0.0,
+                                        "step_frac": ffn_bytes / (wall_d / args.decode_steps) / PEAK_HBM if active else 0.0,
+                                        "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "traffic": None}})
+            log(f"[bench] decode T={Td}: {decode[-1]['ms_per_step']:.4f} ms/step, up {up_d * 1e3:.4f} ms, ffn {ffn_d * 1e3:.4f} ms, active={active}")
+
+    # ---- CPU oracle on a bounded sample -----------------------------------------------------------------
+    cpu = None
+    if args.cpu_sample > 0:
+        import oracle
+        n = min(args.cpu_sample, T)
+        toks = np.arange(n, dtype=np.int32)
+        t0 = time.perf_counter()
+        lg, idx, w, _ = oracle.route(h[:n], W, b, cfg.k, cfg.norm_mode)
+        oracle.layer(h[:n], idx, w, w1, w3, w2, mask, tokens=toks)
+        dt = time.perf_counter() - t0
+        cpu = {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {n} tokens of the prefill batch, route + masked expert FFN + combine, {dt:.1f} s"}
+        log(f"[bench] oracle: {n} tokens in {dt:.1f}s on {cpu['cores']} threads")
+
+    out = {"metric": "MoE-layer tokens/sec (prefill 2048 tok)", "value": value, "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "mixtral-8x7b-shaped layer, prefill 2048 tokens", "d": cfg.d, "experts": cfg.N,
+                      "top_k": cfg.k, "inner": cfg.I, "experts_on_gpu": int(on.sum()), "tokens": T},
+           "roofline": roofline, "cpu_baseline": cpu, "decode": decode}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,19 @@ int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const
                    const uint8_t *expert_mask, void *y, void *workspace, void *stream);
 
 /*
+ * The same computation in two separately launchable halves, for callers that want to time or overlap them:
+ * MOE_FFN_STAGE_UP writes the bf16 inner activations silu(W1 x) * (W3 x) of all rows into the workspace,
+ * MOE_FFN_STAGE_DOWN multiplies them by W2 into y.  A DOWN call must follow an UP call with the same
+ * arguments and workspace on the same stream.  MOE_FFN_STAGE_ALL is moe_expert_ffn.
+ */
+#define MOE_FFN_STAGE_UP   1
+#define MOE_FFN_STAGE_DOWN 2
+#define MOE_FFN_STAGE_ALL  3
+int moe_expert_ffn_stage(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
+                         const int32_t *counts, const void *w1, const void *w3, const void *w2,
+                         const uint8_t *expert_mask, void *y, void *workspace, int stages, void *stream);
+
+/*
  * Weighted combine (Eq. 2, restricted to the experts with G_i = 1):
  *
  *   out[t,:] = sum_{s<k, expert_mask[topk_idx[t,s]] != 0} topk_w[t,s] * y[inv_perm[t*k+s], :]

@@ -16,7 +16,7 @@ FFN_AUTO, FFN_TILED, FFN_SKINNY = 0, 1, 2
 NORM_NONE, NORM_RENORM = 0, 1
 
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
-           "moe_combine", "moe_dense_route", "moe_shared_gate"]
+           "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate"]
 
 
 class MoeShape(C.Structure):
@@ -126,6 +126,19 @@ def moe_expert_ffn(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mas
                                        _ptr(w3, torch.bfloat16), _ptr(w2, torch.bfloat16), _ptr(expert_mask, torch.uint8),
                                        _ptr(y, torch.bfloat16), _ws_ptr(ws), _stream())
     _check(rc, "moe_expert_ffn")
+    return y
+
+
+STAGE_UP, STAGE_DOWN, STAGE_ALL = 1, 2, 3
+
+
+def moe_expert_ffn_stage(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, ws: torch.Tensor, stages: int):
+    rc = load_library().moe_expert_ffn_stage(C.byref(s), _ptr(h, torch.bfloat16), _ptr(perm, torch.int32),
+                                             _ptr(offsets, torch.int32), _ptr(counts, torch.int32),
+                                             _ptr(w1, torch.bfloat16), _ptr(w3, torch.bfloat16), _ptr(w2, torch.bfloat16),
+                                             _ptr(expert_mask, torch.uint8), _ptr(y, torch.bfloat16), _ws_ptr(ws),
+                                             C.c_int(stages), _stream())
+    _check(rc, "moe_expert_ffn_stage")
     return y
 
 

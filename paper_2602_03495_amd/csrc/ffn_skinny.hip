@@ -216,7 +216,7 @@ static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, 
 
 int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                         const int32_t *counts, const void *w1, const void *w3, const void *w2,
-                        const uint8_t *expert_mask, void *y, void *workspace, hipStream_t st)
+                        const uint8_t *expert_mask, void *y, void *workspace, int stages, hipStream_t st)
 {
     const int d = s->d, I = s->I, N = s->N, k = s->k, R = s->T * s->k;
     if (s->T > MOE_SKINNY_MAX_T) return MOE_EUNSUPPORTED;
@@ -227,7 +227,7 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
     const int est_active = N < R ? N : R;
 
     // ---- gate/up projections + SwiGLU ------------------------------------------------------------
-    {
+    if (stages & MOE_FFN_STAGE_UP) {
         const int per = ((d >> 5) + SK_WAVES - 1) / SK_WAVES;
         const int tiles = (I + 15) / 16;
         const int rt = pick_rt(tiles, est_active);
@@ -242,7 +242,7 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         MOE_CHECK_LAUNCH();
     }
     // ---- down projection ---------------------------------------------------------------------------
-    {
+    if (stages & MOE_FFN_STAGE_DOWN) {
         const int total = I >> 5;
         const int nsplit = moe_skinny_nsplit(I);
         const int spb = (total + nsplit - 1) / nsplit;

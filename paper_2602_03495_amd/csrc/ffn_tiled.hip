@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256, 2) void ffn_tiled_kernel(
 
 int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                        const int32_t *counts, const void *w1, const void *w3, const void *w2,
-                       const uint8_t *expert_mask, void *y, void *workspace, hipStream_t st)
+                       const uint8_t *expert_mask, void *y, void *workspace, int stages, hipStream_t st)
 {
     const int d = s->d, I = s->I, N = s->N, k = s->k;
     const long R = (long)s->T * k;
@@ -222,15 +222,15 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     int32_t *sched = (int32_t *)((char *)workspace + L.sched);
     const long max_mt = R / TM + (N < R ? N : R);
 
-    hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
-    MOE_CHECK_LAUNCH();
-    {
+    if (stages & MOE_FFN_STAGE_UP) {
+        hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
+        MOE_CHECK_LAUNCH();
         const long n_nt = (I + 127) / 128;
         hipLaunchKernelGGL(ffn_tiled_kernel<0>, dim3((unsigned)(max_mt * n_nt)), dim3(256), 0, st, d, I, k,
                            (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1, (const uint16_t *)w3, sched, act);
         MOE_CHECK_LAUNCH();
     }
-    {
+    if (stages & MOE_FFN_STAGE_DOWN) {
         const long n_nt = (d + 255) / 256;
         hipLaunchKernelGGL(ffn_tiled_kernel<1>, dim3((unsigned)(max_mt * n_nt)), dim3(256), 0, st, d, I, k,
                            (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr, sched,

@@ -8,9 +8,9 @@ int moe_predict_impl(const moe_shape *, const void *, const float *, const void 
 int moe_dense_route_impl(const moe_shape *, int32_t *, int32_t *, int32_t *, hipStream_t);
 int moe_shared_gate_impl(const moe_shape *, const void *, const void *, float *, hipStream_t);
 int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
-                       const void *, const void *, const uint8_t *, void *, void *, hipStream_t);
+                       const void *, const void *, const uint8_t *, void *, void *, int, hipStream_t);
 int moe_ffn_skinny_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
-                        const void *, const void *, const uint8_t *, void *, void *, hipStream_t);
+                        const void *, const void *, const uint8_t *, void *, void *, int, hipStream_t);
 int moe_combine_impl(const moe_shape *, const void *, const int32_t *, const float *, const int32_t *, const uint8_t *,
                      const void *, int, const float *, void *, hipStream_t);
 
@@ -78,10 +78,11 @@ int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec
                             (hipStream_t)stream);
 }
 
-int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets, const int32_t *counts,
-                   const void *w1, const void *w3, const void *w2, const uint8_t *expert_mask, void *y, void *workspace,
-                   void *stream)
+int moe_expert_ffn_stage(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
+                         const int32_t *counts, const void *w1, const void *w3, const void *w2, const uint8_t *expert_mask,
+                         void *y, void *workspace, int stages, void *stream)
 {
+    if (stages < 1 || stages > MOE_FFN_STAGE_ALL) return MOE_EINVAL;
     int rc = check_shape(s, true);
     if (rc != MOE_OK) return rc;
     if (!h || !perm || !offsets || !counts || !w1 || !w3 || !w2 || !y || !workspace) return MOE_EINVAL;
@@ -90,10 +91,17 @@ int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const
     int path = s->ffn_path;
     if (path == MOE_FFN_AUTO) path = s->T <= MOE_SKINNY_MAX_T ? MOE_FFN_SKINNY : MOE_FFN_TILED;
     if (path == MOE_FFN_SKINNY)
-        return moe_ffn_skinny_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, (hipStream_t)stream);
+        return moe_ffn_skinny_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, stages, (hipStream_t)stream);
     if (path == MOE_FFN_TILED)
-        return moe_ffn_tiled_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, (hipStream_t)stream);
+        return moe_ffn_tiled_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, stages, (hipStream_t)stream);
     return MOE_EINVAL;
+}
+
+int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets, const int32_t *counts,
+                   const void *w1, const void *w3, const void *w2, const uint8_t *expert_mask, void *y, void *workspace,
+                   void *stream)
+{
+    return moe_expert_ffn_stage(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, MOE_FFN_STAGE_ALL, stream);
 }
 
 int moe_combine(const moe_shape *s, const void *y, const int32_t *topk_idx, const float *topk_w, const int32_t *inv_perm,
