@@ -51,6 +51,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
         load_x_frags<MAXS>(xf, h + (size_t)tok * d, valid, s0, ns, g);
     }
     const int i0 = blockIdx.x * (16 * RT);
+    const int last = ns > 0 ? ns - 1 : 0;   // steps past the wave's range re-read its last step against a zero fragment
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         int row = i0 + rt * 16 + i;
@@ -58,13 +59,18 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
         const uint16_t *p1 = w1 + ((size_t)e * I + row) * d + (size_t)s0 * 32 + g * 8;
         const uint16_t *p3 = w3 + ((size_t)e * I + row) * d + (size_t)s0 * 32 + g * 8;
         f32x4 ag = {0.f, 0.f, 0.f, 0.f}, au = {0.f, 0.f, 0.f, 0.f};
+        if (ns > 0) {
+            u32x4 a1[MAXS], a3[MAXS];
 #pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            if (s < ns) {
-                u32x4 a1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p1 + s * 32));
-                u32x4 a3 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p3 + s * 32));
-                ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a1), as_frag(xf[s]), ag, 0, 0, 0);
-                au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a3), as_frag(xf[s]), au, 0, 0, 0);
+            for (int s = 0; s < MAXS; ++s) {
+                const int so = (s < ns ? s : last) * 32;
+                a1[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p1 + so));
+                a3[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p3 + so));
+            }
+#pragma unroll
+            for (int s = 0; s < MAXS; ++s) {
+                ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a1[s]), as_frag(xf[s]), ag, 0, 0, 0);
+                au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a3[s]), as_frag(xf[s]), au, 0, 0, 0);
             }
         }
 #pragma unroll
@@ -121,18 +127,21 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
         load_x_frags<MAXS>(xf, act + (size_t)(off + (valid ? i : 0)) * I, valid, s0, ns, g);
     }
     const int f0 = blockIdx.x * (16 * RT);
+    const int last = ns > 0 ? ns - 1 : 0;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         int row = f0 + rt * 16 + i;
         if (row >= d) row = d - 1;
         const uint16_t *p2 = w2 + ((size_t)e * d + row) * I + (size_t)s0 * 32 + g * 8;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (ns > 0) {
+            u32x4 a[MAXS];
 #pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            if (s < ns) {
-                u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p2 + s * 32));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a), as_frag(xf[s]), acc, 0, 0, 0);
-            }
+            for (int s = 0; s < MAXS; ++s)
+                a[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p2 + (s < ns ? s : last) * 32));
+#pragma unroll
+            for (int s = 0; s < MAXS; ++s)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[s]), as_frag(xf[s]), acc, 0, 0, 0);
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[wave][rt][lane * 4 + r] = acc[r];
@@ -233,12 +242,9 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         const int rt = pick_rt(tiles, est_active);
         dim3 grid((tiles + rt - 1) / rt, N);
         const uint16_t *hp = (const uint16_t *)h, *p1 = (const uint16_t *)w1, *p3 = (const uint16_t *)w3;
-        if (per <= 8)
-            launch_up<8>(rt, grid, st, d, k, I, hp, perm, offsets, counts, p1, p3, expert_mask, act);
-        else if (per <= 16)
-            launch_up<16>(rt, grid, st, d, k, I, hp, perm, offsets, counts, p1, p3, expert_mask, act);
-        else
-            launch_up<32>(rt, grid, st, d, k, I, hp, perm, offsets, counts, p1, p3, expert_mask, act);
+#define UP(n) case n: launch_up<4 * n>(rt, grid, st, d, k, I, hp, perm, offsets, counts, p1, p3, expert_mask, act); break;
+        switch ((per + 3) / 4) { UP(1) UP(2) UP(3) UP(4) UP(5) UP(6) UP(7) UP(8) default: return MOE_EUNSUPPORTED; }
+#undef UP
         MOE_CHECK_LAUNCH();
     }
     // ---- down projection ---------------------------------------------------------------------------
@@ -252,26 +258,18 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         dim3 grid((tiles + rt - 1) / rt, nsplit, N);
         const uint16_t *p2 = (const uint16_t *)w2;
         uint16_t *yp = (uint16_t *)y;
+#define DN(n, direct) case n: launch_down<4 * n, direct>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial); break;
         if (nsplit == 1) {
-            if (per <= 8)
-                launch_down<8, true>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
-            else if (per <= 16)
-                launch_down<16, true>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
-            else
-                launch_down<32, true>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
+            switch ((per + 3) / 4) { DN(1, true) DN(2, true) DN(3, true) DN(4, true) DN(5, true) DN(6, true) DN(7, true) DN(8, true) default: return MOE_EUNSUPPORTED; }
             MOE_CHECK_LAUNCH();
         } else {
-            if (per <= 8)
-                launch_down<8, false>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
-            else if (per <= 16)
-                launch_down<16, false>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
-            else
-                launch_down<32, false>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial);
+            switch ((per + 3) / 4) { DN(1, false) DN(2, false) DN(3, false) DN(4, false) DN(5, false) DN(6, false) DN(7, false) DN(8, false) default: return MOE_EUNSUPPORTED; }
             MOE_CHECK_LAUNCH();
             hipLaunchKernelGGL(skinny_finish_kernel, dim3(MOE_SKINNY_MAX_T, N), dim3(256), 0, st, d, R, nsplit, partial,
                                offsets, counts, expert_mask, yp);
             MOE_CHECK_LAUNCH();
         }
+#undef DN
     }
     return MOE_OK;
 }
