@@ -20,8 +20,8 @@
  *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics; the
  *     token permutation is stable).
  *
- * Shape limits: 1 <= k <= 8, k <= N <= 128, T >= 1, T*k < 2^31, d a multiple of 128 (<= 8192),
- * I a multiple of 32.
+ * Shape limits: 1 <= k <= 8, k <= N <= 128, T >= 1, T*k < 2^31, T*d < 2^31, d a multiple of 128 (<= 8192),
+ * I a multiple of 128.
  */
 #ifndef MOE_LAYER_H
 #define MOE_LAYER_H
@@ -108,6 +108,19 @@ int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec
                          void *workspace, void *stream);
 
 /*
+ * Expert weights are consumed in a packed, MFMA-fragment-ordered layout (the expert weights are static, so this
+ * is done once when they are loaded).  moe_pack_weights converts n_mats row-major [rows, K] bf16 matrices:
+ *
+ *   packed[m][rb][kb][l][j] = src[m][16*rb + (l % 16)][32*kb + 8*(l / 16) + j]
+ *   for rb < rows/16, kb < K/32, l < 64, j < 8
+ *
+ * i.e. every 1 KB block holds 16 rows x 32 k in the lane order of the A operand of v_mfma_f32_16x16x32_bf16.
+ * rows must be a multiple of 16 and K a multiple of 32; src and dst [device], distinct, 16-byte aligned.
+ * w1 and w3 are packed with (n_mats = N, rows = I, K = d), w2 with (n_mats = N, rows = d, K = I).
+ */
+int moe_pack_weights(int n_mats, int rows, int K, const void *src, void *dst, void *stream);
+
+/*
  * Expert FFNs of the experts placed on this GPU (the experts with G_i = 1 in Section "Greedy
  * Assignment Strategy"; "each activated expert calculates the corresponding output using x",
  * Section "Mixture of Experts (MoE)").  For every expert e with expert_mask[e] != 0 and
@@ -118,7 +131,8 @@ int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec
  * bf16 inputs, fp32 accumulation; the inner activation is rounded to bf16 once before the second
  * product.  Rows of experts that are masked off are not written.
  * h [T,d] bf16; perm [T*k], offsets [N+1], counts [N] int32 as produced by moe_route (or
- * moe_dense_route); w1, w3 [N,I,d] bf16; w2 [N,d,I] bf16; expert_mask [N] uint8 (NULL = all on);
+ * moe_dense_route); w1, w3: [N,I,d] bf16 and w2: [N,d,I] bf16, all three PACKED by moe_pack_weights;
+ * expert_mask [N] uint8 (NULL = all on);
  * y [T*k,d] bf16 out, in permuted row order: all [device].
  */
 int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,

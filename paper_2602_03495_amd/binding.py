@@ -16,7 +16,7 @@ FFN_AUTO, FFN_TILED, FFN_SKINNY = 0, 1, 2
 NORM_NONE, NORM_RENORM = 0, 1
 
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
-           "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate"]
+           "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights"]
 
 
 class MoeShape(C.Structure):
@@ -149,6 +149,17 @@ def moe_combine(s: MoeShape, y, topk_idx, topk_w, inv_perm, expert_mask, shared_
                                     _ptr(shared_scale, torch.float32), _ptr(out, torch.bfloat16), _stream())
     _check(rc, "moe_combine")
     return out
+
+
+def moe_pack_weights(src: torch.Tensor, dst: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Pack row-major [n_mats, rows, K] bf16 matrices into the MFMA-fragment order the FFN kernels read."""
+    n_mats, rows, K = src.shape
+    if dst is None:
+        dst = torch.empty_like(src)
+    rc = load_library().moe_pack_weights(C.c_int(n_mats), C.c_int(rows), C.c_int(K), _ptr(src, torch.bfloat16),
+                                         _ptr(dst, torch.bfloat16), _stream())
+    _check(rc, "moe_pack_weights")
+    return dst
 
 
 def moe_dense_route(s: MoeShape, counts, offsets, perm):

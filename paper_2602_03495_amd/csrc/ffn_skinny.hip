@@ -1,7 +1,9 @@
 // Expert FFN for decode-sized batches (at most 16 rows per expert) on gfx950: a weight-streaming path.
 //
-// Every weight element of a touched, masked-on expert is read from HBM exactly once, by a 16-byte load that
-// goes straight from global memory into the A operand of a bf16 MFMA 16x16x32 (16 weight rows x 32 k); the
+// Every weight element of a touched, masked-on expert is read from HBM exactly once.  Weights are in the
+// packed layout of moe_pack_weights, where one A operand of a bf16 MFMA 16x16x32 (16 weight rows x 32 k) is
+// 1 KB of contiguous memory in lane order, so a wave's 16-byte-per-lane load is one fully coalesced 1 KB read
+// that goes straight from global memory into the MFMA; the
 // B operand holds the (<= 16) token rows of that expert and lives in registers for the whole block, so the
 // inner loop is "global_load, mfma" and nothing else.  K is split over the 4 waves of a block (and, for the
 // long down projection, over several blocks); partial 16x16 tiles are reduced through LDS (and through an
@@ -54,16 +56,17 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
     const int last = ns > 0 ? ns - 1 : 0;   // steps past the wave's range re-read its last step against a zero fragment
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-        int row = i0 + rt * 16 + i;
-        if (row >= I) row = I - 1;
-        const uint16_t *p1 = w1 + ((size_t)e * I + row) * d + (size_t)s0 * 32 + g * 8;
-        const uint16_t *p3 = w3 + ((size_t)e * I + row) * d + (size_t)s0 * 32 + g * 8;
+        int rb = (i0 >> 4) + rt;                            // 16-row block of W1 / W3
+        if (rb * 16 >= I) rb = (I >> 4) - 1;
+        const size_t fo = (size_t)e * I * d + ((size_t)rb * total + s0) * 512 + lane * 8;
+        const uint16_t *p1 = w1 + fo;
+        const uint16_t *p3 = w3 + fo;
         f32x4 ag = {0.f, 0.f, 0.f, 0.f}, au = {0.f, 0.f, 0.f, 0.f};
         if (ns > 0) {
             u32x4 a1[MAXS], a3[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; ++s) {
-                const int so = (s < ns ? s : last) * 32;
+                const int so = (s < ns ? s : last) * 512;
                 a1[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p1 + so));
                 a3[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p3 + so));
             }
@@ -130,15 +133,15 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
     const int last = ns > 0 ? ns - 1 : 0;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-        int row = f0 + rt * 16 + i;
-        if (row >= d) row = d - 1;
-        const uint16_t *p2 = w2 + ((size_t)e * d + row) * I + (size_t)s0 * 32 + g * 8;
+        int rb = (f0 >> 4) + rt;                            // 16-row block of W2
+        if (rb * 16 >= d) rb = (d >> 4) - 1;
+        const uint16_t *p2 = w2 + (size_t)e * d * I + ((size_t)rb * total + s0) * 512 + lane * 8;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (ns > 0) {
             u32x4 a[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; ++s)
-                a[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p2 + (s < ns ? s : last) * 32));
+                a[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p2 + (s < ns ? s : last) * 512));
 #pragma unroll
             for (int s = 0; s < MAXS; ++s)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[s]), as_frag(xf[s]), acc, 0, 0, 0);

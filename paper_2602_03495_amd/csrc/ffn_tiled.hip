@@ -1,27 +1,37 @@
-// Grouped SwiGLU expert FFN for prefill-sized batches on gfx950: LDS-tiled bf16 MFMA 32x32x16 GEMMs.
+// Grouped SwiGLU expert FFN for prefill-sized batches on gfx950.
 //
-// Two grouped "NT" GEMMs (both operands K-contiguous), each over the rows of the masked-on, non-empty experts:
+// Two grouped GEMMs over the rows of the masked-on, non-empty experts:
 //   up:    act[p, i] = silu(x_p . W1_e[i,:]) * (x_p . W3_e[i,:])      x_p = h[perm[p]/k, :] gathered in the tile load
 //   down:  y[p, f]   = act[p,:] . W2_e[f,:]
-// A work item is (expert, 128-row token tile, 256-row weight tile); for "up" the weight tile is 128 rows of
-// W1 and the same 128 rows of W3, so that a thread ends up holding a gate value and its up value and the
-// SwiGLU is applied in registers.  The item list is built on the device from counts/offsets/mask by
-// tile_schedule_kernel (no host round trip); empty and masked-off experts get no items.  The MFMA takes the
-// weight rows as its A operand and the token rows as B, so each lane owns 4 consecutive output columns of one
-// token and stores them as one 8-byte word.
 //
-// Launch order: block ids are dealt round-robin to the 8 XCDs, so ids are remapped to give each XCD (its own
-// L2) a contiguous run of items, ordered expert-major, then weight tile, then token tile: the token tiles
-// that share a weight tile run next to each other on one XCD and the weight tile is fetched from HBM once.
+// Design (what the counters said while this was built): with 128-row token tiles the kernel is bound by L2
+// request throughput, not by MFMA issue, so the data path is shaped to ask L2 for as little as possible, in
+// full 128-byte lines:
+//   * Weights are consumed in the packed layout of moe_pack_weights: one MFMA 16x16x32 A fragment (16 weight
+//     rows x 32 k) is 1 KB of contiguous memory in lane order.  Every wave owns a private set of weight rows,
+//     so weights never pass through LDS: global_load_dwordx4 -> VGPR -> MFMA, prefetched 3 k32-steps ahead in
+//     4 rotating register sets (the compiler's own vmcnt tracking keeps ~12 loads per wave in flight).
+//   * The token tile (128 rows, shared by all 8 waves) is staged through LDS in k64 stages (16 KB each,
+//     double buffered, 128-byte global requests), loaded two stages ahead so that waiting for it never
+//     drains the weight prefetch queue (vmcnt retires in order).
+//   * 8 waves per block (2 per SIMD, 128 fp32 accumulator registers each): one wave's barrier or load wait is
+//     covered by the other's MFMAs, and the accumulators stay in place (no AGPR shuffling).
+//   * The MFMA takes weight rows as A and token rows as B, so a lane ends up with 4 consecutive output columns
+//     of one token: SwiGLU is applied in registers and the result leaves as one 8-byte store.
+// A work item is (expert, 128-row token tile, weight tile); the item list is built on the device from
+// counts/offsets/mask (tile_schedule_kernel), so empty and masked-off experts cost nothing and there is no host
+// round trip.  Block ids are remapped so that every XCD (own L2) works on a contiguous run of items ordered
+// expert-major, weight tile, token tile: the token tiles that share a weight tile run side by side on one XCD.
+// Each item walks K as a ring starting at a tile-dependent offset, which spreads concurrently running tiles
+// over the address space; the summation order is a function of (expert, weight tile) only, so results are
+// reproducible.
 #include "moe_common.h"
 
 #define TM MOE_TILE_M     // token rows per tile
-#define TW 256            // weight rows per tile
-#define TK 64             // k per LDS stage
-#define LDS_LD 72         // LDS row pitch in bf16 (64 + 8 pad: 144 B keeps 16-lane b128 reads conflict-free)
 #define NUM_XCD 8
+#define TILED_THREADS 512
 
-// sched layout: int32 hdr[4] = {n_mtiles, 0, 0, 0}; then int4 per global token tile {expert, first_tile, n_tiles_of_expert, 0}
+// sched layout: int32 hdr[4] = {n_token_tiles, 0, 0, 0}; then int4 per token tile {expert, first_tile, n_tiles_of_expert, 0}
 __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, const int32_t *__restrict__ counts,
                                                                         const uint8_t *__restrict__ mask,
                                                                         int32_t *__restrict__ sched)
@@ -49,21 +59,26 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
     }
 }
 
-template <int MODE>   // 0: up (W1|W3 + SwiGLU -> act), 1: down (W2 -> y)
-__global__ __launch_bounds__(256, 2) void ffn_tiled_kernel(
+// MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
+// MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
+// Weight tile of a block: 8 waves x NF fragments x 16 rows.
+template <int MODE, int NF>
+__global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
-    const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: w1, w3; MODE 1: w2, unused
+    const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
     const int32_t *__restrict__ sched, uint16_t *__restrict__ out)      // MODE 0: act [R,I]; MODE 1: y [R,d]
 {
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[TM * LDS_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[TW * LDS_LD];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
 
-    const int K = MODE == 0 ? d : I;          // contraction length
-    const int NOUT = MODE == 0 ? I : d;       // output columns
-    const int n_nt = MODE == 0 ? (I + 127) / 128 : (d + 255) / 256;
+    constexpr int HF = MODE == 0 ? NF / 2 : NF;           // fragments per matrix per wave
+    constexpr int WAVE_COLS = HF * 16;                     // output columns a wave produces
+    constexpr int NT_COLS = 8 * WAVE_COLS;                 // output columns per block
+    const int K = MODE == 0 ? d : I;
+    const int NOUT = MODE == 0 ? I : d;
+    const int n_nt = (NOUT + NT_COLS - 1) / NT_COLS;
 
-    // ---- which item ----------------------------------------------------------------------------
+    // ---- which item -------------------------------------------------------------------------------
     const int n_mt = sched[0];
     const int total = n_mt * n_nt;
     const int pid = blockIdx.x;
@@ -81,130 +96,136 @@ __global__ __launch_bounds__(256, 2) void ffn_tiled_kernel(
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;
     nrows = nrows > TM ? TM : nrows;
-    const int n0 = nt * (MODE == 0 ? 128 : 256);
+    const int n0 = nt * NT_COLS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int li = lane & 15, lg = lane >> 4;
+    const int kb_n = K / 32;                               // k32 blocks per weight row block
+    const size_t rb_stride = (size_t)kb_n * 512;           // elements between consecutive 16-row blocks
 
-    // ---- global -> LDS staging: thread owns 16-byte chunk (tid%8) of rows tid/8 + 32*i --------------
-    const int lrow = tid >> 3, lchunk = tid & 7;
-    const uint16_t *xptr[4];
+    // ---- this wave's weight fragments: consecutive row blocks, so one pointer per matrix + a uniform stride
+    const uint16_t *wp0, *wp1;
+    {
+        int col = n0 + wave * WAVE_COLS;
+        if (col >= NOUT) col = NOUT - WAVE_COLS;           // a wave past the ragged edge recomputes the last columns
+        const size_t mat = (size_t)e * d * I + (size_t)(col >> 4) * rb_stride + lane * 8;
+        wp0 = wa + mat;
+        wp1 = MODE == 0 ? wb + mat : wp0;
+    }
+    // ---- token tile loader: thread -> rows tid/8 + 64 j (j < 2), 16-byte chunk tid%8 of the 128-byte k64 segment
+    const int xc = tid & 7;
+    uint32_t xo[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int r = lrow + 32 * i;
+    for (int j = 0; j < 2; ++j) {
+        int r = (tid >> 3) + 64 * j;
         if (r >= nrows) r = nrows - 1;
         if (MODE == 0)
-            xptr[i] = xsrc + (size_t)(perm[row0 + r] / k) * d + lchunk * 8;
+            xo[j] = (uint32_t)(perm[row0 + r] / k) * (uint32_t)d + xc * 8;
         else
-            xptr[i] = xsrc + (size_t)(row0 + r) * I + lchunk * 8;
+            xo[j] = (uint32_t)r * (uint32_t)I + xc * 8;
     }
-    const uint16_t *wptr[8];
+    const uint16_t *xbase = MODE == 0 ? xsrc : xsrc + (size_t)row0 * I;
+    uint16_t *xw = &Xs[0][xc >> 2][(tid >> 3) * 32 + (xc & 3) * 8];   // + buffer * 2*TM*32 + j * 64 rows
+    const uint16_t *xrd = &Xs[0][0][li * 32 + lg * 8];               // + buffer * 2*TM*32 + half * TM*32 + t * 16 rows
+
+    f32x4 acc[NF][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int r = lrow + 32 * i;
-        if (MODE == 0) {
-            int col = n0 + (r & 127);
-            if (col >= I) col = I - 1;
-            wptr[i] = (r < 128 ? wa : wb) + ((size_t)e * I + col) * d + lchunk * 8;
-        } else {
-            int col = n0 + r;
-            if (col >= d) col = d - 1;
-            wptr[i] = wa + ((size_t)e * d + col) * I + lchunk * 8;
-        }
-    }
-    u32x4 xr[4], wr[8];
-#define GLOAD(k0)                                                                                   \
-    do {                                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) xr[i_] = *reinterpret_cast<const u32x4 *>(xptr[i_] + (k0)); \
-        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) wr[i_] = *reinterpret_cast<const u32x4 *>(wptr[i_] + (k0)); \
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[f][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nk = kb_n;          // k32 steps (a multiple of 4: K % 128 == 0)
+    const int nst = nk / 2;       // k64 stages
+    const int st0 = (int)(((unsigned)nt * 7u + (unsigned)e * 3u) % (unsigned)nst);   // where this item's K ring starts
+    u32x4 wr[4][NF];              // W(step) lives in set step % 4, loaded 3 steps ahead
+    u32x4 xg[2][2];               // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
+    bf16x8 xf[8];
+
+#define KSTEP(s) (((s) + 2 * st0) % nk)
+#define KSTAGE(st) (((st) + st0) % nst)
+#define WLOAD(set, s)                                                                            \
+    do {                                                                                         \
+        const size_t ko_ = (size_t)KSTEP(s) * 512;                                               \
+        _Pragma("unroll") for (int f = 0; f < HF; ++f) {                                         \
+            wr[set][f] = *reinterpret_cast<const u32x4 *>(wp0 + f * rb_stride + ko_);            \
+            if (MODE == 0) wr[set][f + HF] = *reinterpret_cast<const u32x4 *>(wp1 + f * rb_stride + ko_); \
+        }                                                                                        \
     } while (0)
-#define LSTORE()                                                                                    \
-    do {                                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
-            *reinterpret_cast<u32x4 *>(&Xs[(lrow + 32 * i_) * LDS_LD + lchunk * 8]) = xr[i_];       \
-        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_)                                            \
-            *reinterpret_cast<u32x4 *>(&Ws[(lrow + 32 * i_) * LDS_LD + lchunk * 8]) = wr[i_];       \
+#define XLOAD(set, st)                                                                           \
+    do {                                                                                         \
+        const size_t ko_ = (size_t)KSTAGE(st) * 64;                                              \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                            \
+            xg[set][j] = *reinterpret_cast<const u32x4 *>(xbase + xo[j] + ko_);                  \
+    } while (0)
+#define XSTORE(buf)                                                                              \
+    do {                                                                                         \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                            \
+            *reinterpret_cast<u32x4 *>(xw + (buf) * (2 * TM * 32) + j * (64 * 32)) = xg[buf][j]; \
+    } while (0)
+#define XREAD(buf, half)                                                                         \
+    do {                                                                                         \
+        _Pragma("unroll") for (int t = 0; t < 8; ++t)                                            \
+            xf[t] = as_frag(*reinterpret_cast<const u32x4 *>(xrd + (buf) * (2 * TM * 32) + (half) * (TM * 32) + t * (16 * 32))); \
+    } while (0)
+#define MFMAS(set)                                                                               \
+    do {                                                                                         \
+        _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
+            _Pragma("unroll") for (int t = 0; t < 8; ++t)                                        \
+                acc[f][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(wr[set][f]), xf[t], acc[f][t], 0, 0, 0); \
+    } while (0)
+    // stage st: k32 steps 2 st (weight set ws_) and 2 st + 1; X(st) is in LDS buffer st % 2
+#define STAGE(buf, ws_, st)                                                                      \
+    do {                                                                                         \
+        __builtin_amdgcn_s_waitcnt(0xC07F);      /* lgkmcnt(0): this thread's LDS writes of X(st) have landed */ \
+        __builtin_amdgcn_s_barrier();                                                            \
+        XLOAD(buf, (st) + 2);                     /* register set st%2 held X(st), which is in LDS now */         \
+        WLOAD(((ws_) + 3) & 3, 2 * (st) + 3);                                                    \
+        XREAD(buf, 0);                                                                           \
+        MFMAS(ws_);                                                                              \
+        WLOAD(((ws_) + 4) & 3, 2 * (st) + 4);                                                    \
+        XREAD(buf, 1);                                                                           \
+        MFMAS(((ws_) + 1) & 3);                                                                  \
+        XSTORE((buf) ^ 1);                        /* X(st+1) -> the other LDS buffer */          \
     } while (0)
 
-    f32x16 acc[2][2][2];   // [weight group][weight frag][token frag]
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) acc[a][b][c][q] = 0.f;
-
-    const int l32 = lane & 31, kh = lane >> 5;
-    const uint16_t *ws_base = &Ws[(wn * 64 + l32) * LDS_LD + kh * 8];
-    const uint16_t *xs_base = &Xs[(wm * 64 + l32) * LDS_LD + kh * 8];
-
-    GLOAD(0);
-    LSTORE();
-    __syncthreads();
-    const int nk = K / TK;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) GLOAD((kt + 1) * TK);
-#pragma unroll
-        for (int kk = 0; kk < TK / 16; ++kk) {
-            bf16x8 wf[2][2], xf[2];
-#pragma unroll
-            for (int grp = 0; grp < 2; ++grp)
-#pragma unroll
-                for (int fi = 0; fi < 2; ++fi)
-                    wf[grp][fi] = as_frag(*reinterpret_cast<const u32x4 *>(ws_base + (grp * 128 + fi * 32) * LDS_LD + kk * 16));
-#pragma unroll
-            for (int fj = 0; fj < 2; ++fj)
-                xf[fj] = as_frag(*reinterpret_cast<const u32x4 *>(xs_base + (fj * 32) * LDS_LD + kk * 16));
-#pragma unroll
-            for (int grp = 0; grp < 2; ++grp)
-#pragma unroll
-                for (int fi = 0; fi < 2; ++fi)
-#pragma unroll
-                    for (int fj = 0; fj < 2; ++fj)
-                        acc[grp][fi][fj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[grp][fi], xf[fj], acc[grp][fi][fj], 0, 0, 0);
-        }
-        __syncthreads();
-        if (kt + 1 < nk) {
-            LSTORE();
-            __syncthreads();
-        }
+    XLOAD(0, 0);
+    XLOAD(1, 1);
+    WLOAD(0, 0);
+    WLOAD(1, 1);
+    WLOAD(2, 2);
+    XSTORE(0);
+    for (int st = 0; st < nst; st += 2) {
+        STAGE(0, 0, st);
+        STAGE(1, 2, st + 1);
     }
+#undef STAGE
+#undef MFMAS
+#undef XREAD
+#undef XSTORE
+#undef XLOAD
+#undef WLOAD
+#undef KSTAGE
+#undef KSTEP
 
-    // ---- epilogue: lane holds, per fragment, columns 8b + 4*(lane/32) + 0..3 of token row lane%32 ----
+    // ---- epilogue: in every 16x16 tile a lane holds weight rows 4*lg + 0..3 (= output columns) of token li
+    const int colw = n0 + wave * WAVE_COLS;
+    if (colw >= NOUT) return;                               // wave past the ragged edge: its columns were recomputed only
 #pragma unroll
-    for (int fj = 0; fj < 2; ++fj) {
-        const int tr = wm * 64 + fj * 32 + l32;
-        if (tr >= nrows) continue;
-        uint16_t *orow = out + (size_t)(row0 + tr) * NOUT;
+    for (int t = 0; t < 8; ++t) {
+        const int tr = t * 16 + li;
+        if (tr < nrows) {
+            uint16_t *orow = out + (size_t)(row0 + tr) * NOUT + colw + 4 * lg;
 #pragma unroll
-        for (int fi = 0; fi < 2; ++fi) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int wrow = wn * 64 + fi * 32 + 8 * b + 4 * kh;
+            for (int f = 0; f < HF; ++f) {
+                u32x2 o;
                 if (MODE == 0) {
-                    const int col = n0 + wrow;
-                    if (col < I) {
-                        u32x2 o;
-                        o.x = pack_bf16x2(silu_mul(acc[0][fi][fj][4 * b + 0], acc[1][fi][fj][4 * b + 0]),
-                                          silu_mul(acc[0][fi][fj][4 * b + 1], acc[1][fi][fj][4 * b + 1]));
-                        o.y = pack_bf16x2(silu_mul(acc[0][fi][fj][4 * b + 2], acc[1][fi][fj][4 * b + 2]),
-                                          silu_mul(acc[0][fi][fj][4 * b + 3], acc[1][fi][fj][4 * b + 3]));
-                        *reinterpret_cast<u32x2 *>(orow + col) = o;
-                    }
+                    o.x = pack_bf16x2(silu_mul(acc[f][t][0], acc[f + HF][t][0]), silu_mul(acc[f][t][1], acc[f + HF][t][1]));
+                    o.y = pack_bf16x2(silu_mul(acc[f][t][2], acc[f + HF][t][2]), silu_mul(acc[f][t][3], acc[f + HF][t][3]));
                 } else {
-#pragma unroll
-                    for (int grp = 0; grp < 2; ++grp) {
-                        const int col = n0 + grp * 128 + wrow;
-                        if (col < d) {
-                            u32x2 o;
-                            o.x = pack_bf16x2(acc[grp][fi][fj][4 * b + 0], acc[grp][fi][fj][4 * b + 1]);
-                            o.y = pack_bf16x2(acc[grp][fi][fj][4 * b + 2], acc[grp][fi][fj][4 * b + 3]);
-                            *reinterpret_cast<u32x2 *>(orow + col) = o;
-                        }
-                    }
+                    o.x = pack_bf16x2(acc[f][t][0], acc[f][t][1]);
+                    o.y = pack_bf16x2(acc[f][t][2], acc[f][t][3]);
                 }
+                *reinterpret_cast<u32x2 *>(orow + f * 16) = o;
             }
         }
     }
@@ -216,7 +237,6 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
 {
     const int d = s->d, I = s->I, N = s->N, k = s->k;
     const long R = (long)s->T * k;
-    if (d % TK != 0 || I % TK != 0) return MOE_EUNSUPPORTED;
     moe_ws_layout L = moe_ws(s);
     uint16_t *act = (uint16_t *)((char *)workspace + L.act);
     int32_t *sched = (int32_t *)((char *)workspace + L.sched);
@@ -225,16 +245,25 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     if (stages & MOE_FFN_STAGE_UP) {
         hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
         MOE_CHECK_LAUNCH();
-        const long n_nt = (I + 127) / 128;
-        hipLaunchKernelGGL(ffn_tiled_kernel<0>, dim3((unsigned)(max_mt * n_nt)), dim3(256), 0, st, d, I, k,
+        const long n_nt = (I + 255) / 256;
+        hipLaunchKernelGGL((ffn_tiled_kernel<0, 4>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
                            (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1, (const uint16_t *)w3, sched, act);
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_DOWN) {
-        const long n_nt = (d + 255) / 256;
-        hipLaunchKernelGGL(ffn_tiled_kernel<1>, dim3((unsigned)(max_mt * n_nt)), dim3(256), 0, st, d, I, k,
-                           (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr, sched,
-                           (uint16_t *)y);
+        // 512-column tiles when that still gives every compute unit a block, else 256-column tiles
+        const long est_mt = (R + TM - 1) / TM;
+        if (est_mt * ((d + 511) / 512) >= 200) {
+            const long n_nt = (d + 511) / 512;
+            hipLaunchKernelGGL((ffn_tiled_kernel<1, 4>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
+                               (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr,
+                               sched, (uint16_t *)y);
+        } else {
+            const long n_nt = (d + 255) / 256;
+            hipLaunchKernelGGL((ffn_tiled_kernel<1, 2>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
+                               (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr,
+                               sched, (uint16_t *)y);
+        }
         MOE_CHECK_LAUNCH();
     }
     return MOE_OK;

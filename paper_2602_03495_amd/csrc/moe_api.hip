@@ -14,6 +14,8 @@ int moe_ffn_skinny_impl(const moe_shape *, const void *, const int32_t *, const 
 int moe_combine_impl(const moe_shape *, const void *, const int32_t *, const float *, const int32_t *, const uint8_t *,
                      const void *, int, const float *, void *, hipStream_t);
 
+int moe_pack_weights_impl(int, int, int, const void *, void *, hipStream_t);
+
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // sizes every entry point relies on
@@ -23,7 +25,8 @@ static int check_shape(const moe_shape *s, bool need_I)
     if (s->T < 1 || s->N < 1 || s->N > MOE_MAX_EXPERTS || s->k < 1 || s->k > MOE_MAX_TOPK || s->k > s->N) return MOE_EINVAL;
     if ((long long)s->T * s->k >= (1ll << 31)) return MOE_EINVAL;
     if (s->d < 128 || s->d > 8192 || s->d % 128 != 0) return MOE_EINVAL;
-    if (need_I && (s->I < 32 || s->I % 32 != 0)) return MOE_EINVAL;
+    if (need_I && (s->I < 128 || s->I % 128 != 0)) return MOE_EINVAL;
+    if ((long long)s->T * s->d >= (1ll << 31)) return MOE_EINVAL;
     return MOE_OK;
 }
 
@@ -115,6 +118,13 @@ int moe_combine(const moe_shape *s, const void *y, const int32_t *topk_idx, cons
     if (n_shared < 0 || (shared_y && n_shared < 1)) return MOE_EINVAL;
     return moe_combine_impl(s, y, topk_idx, topk_w, inv_perm, expert_mask, shared_y, n_shared, shared_scale, out,
                             (hipStream_t)stream);
+}
+
+int moe_pack_weights(int n_mats, int rows, int K, const void *src, void *dst, void *stream)
+{
+    if (n_mats < 1 || rows < 16 || rows % 16 != 0 || K < 32 || K % 32 != 0) return MOE_EINVAL;
+    if (!src || !dst || src == dst || !aligned16(src) || !aligned16(dst)) return MOE_EINVAL;
+    return moe_pack_weights_impl(n_mats, rows, K, src, dst, (hipStream_t)stream);
 }
 
 int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32_t *perm, void *stream)

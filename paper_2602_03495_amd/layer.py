@@ -27,23 +27,28 @@ def from_device_bf16(t: torch.Tensor) -> np.ndarray:
 class LayerWeights:
     gate_w: torch.Tensor                 # [N,d] bf16
     gate_bias: Optional[torch.Tensor]    # [N] fp32
-    w1: torch.Tensor                     # [N,I,d] bf16
-    w3: torch.Tensor                     # [N,I,d] bf16
-    w2: torch.Tensor                     # [N,d,I] bf16
-    sw1: Optional[torch.Tensor] = None   # [S,Is,d]
+    w1: torch.Tensor                     # [N,I,d] bf16, packed by moe_pack_weights
+    w3: torch.Tensor                     # [N,I,d] bf16, packed
+    w2: torch.Tensor                     # [N,d,I] bf16, packed
+    sw1: Optional[torch.Tensor] = None   # [S,Is,d] packed
     sw3: Optional[torch.Tensor] = None
-    sw2: Optional[torch.Tensor] = None   # [S,d,Is]
+    sw2: Optional[torch.Tensor] = None   # [S,d,Is] packed
     w_sg: Optional[torch.Tensor] = None  # [d] bf16 (sigmoid-gated shared expert)
 
     @staticmethod
     def upload(gate_w, gate_bias, w1, w3, w2, shared=None, device="cuda") -> "LayerWeights":
+        """Upload row-major bf16 bit patterns and pack the expert matrices on the device (one time)."""
+        def packed(bits):
+            return B.moe_pack_weights(to_device_bf16(bits, device))
+
         lw = LayerWeights(to_device_bf16(gate_w, device),
                           None if gate_bias is None else torch.from_numpy(np.asarray(gate_bias, np.float32)).to(device),
-                          to_device_bf16(w1, device), to_device_bf16(w3, device), to_device_bf16(w2, device))
+                          packed(w1), packed(w3), packed(w2))
         if shared is not None:
             sw1, sw3, sw2, w_sg = shared
-            lw.sw1, lw.sw3, lw.sw2 = (to_device_bf16(a, device) for a in (sw1, sw3, sw2))
+            lw.sw1, lw.sw3, lw.sw2 = (packed(a) for a in (sw1, sw3, sw2))
             lw.w_sg = None if w_sg is None else to_device_bf16(w_sg, device)
+        torch.cuda.synchronize()
         return lw
 
 

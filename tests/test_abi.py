@@ -34,7 +34,7 @@ def lib():
 def test_header_declares_the_four_named_calls():
     names = declared_functions()
     for n in ("moe_route", "moe_predict_workload", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
-              "moe_strerror", "moe_dense_route", "moe_shared_gate"):
+              "moe_strerror", "moe_dense_route", "moe_shared_gate", "moe_pack_weights", "moe_expert_ffn_stage"):
         assert n in names
 
 
@@ -72,7 +72,7 @@ def test_workspace_bytes_and_shape_validation(lib):
                 Shape(16, 4096, 64, 9, 14336, 0),    # k above the supported maximum
                 Shape(16, 4100, 8, 2, 14336, 0),     # d not a multiple of 128
                 Shape(16, 16384, 8, 2, 14336, 0),    # d too large
-                Shape(16, 4096, 8, 2, 100, 0)):      # I not a multiple of 32
+                Shape(16, 4096, 8, 2, 160, 0)):      # I not a multiple of 128
         assert lib.moe_workspace_bytes(C.byref(bad), C.byref(n)) == MOE_EINVAL
 
 
@@ -97,3 +97,6 @@ def test_entry_points_reject_null_and_misaligned_pointers_before_launching(lib):
     assert lib.moe_combine(C.byref(s), p, p, p, p, z, p, 0, z, p, z) == MOE_EINVAL                # shared_y without count
     assert lib.moe_dense_route(C.byref(s), p, p, p, z) == MOE_EINVAL                              # needs k == N
     assert lib.moe_shared_gate(C.byref(s), p, z, p, z) == MOE_EINVAL
+    assert lib.moe_pack_weights(8, 500, 256, p, C.c_void_p(0x2000), z) == MOE_EINVAL              # rows not a multiple of 16
+    assert lib.moe_pack_weights(8, 512, 250, p, C.c_void_p(0x2000), z) == MOE_EINVAL              # K not a multiple of 32
+    assert lib.moe_pack_weights(8, 512, 256, p, p, z) == MOE_EINVAL                               # in place

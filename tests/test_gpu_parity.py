@@ -32,8 +32,8 @@ def _np(t):
 SMALL = {
     "tiny": wl.CONFIGS["tiny"],
     "mixtral_s": wl.scaled(wl.CONFIGS["mixtral"], d=512, I=1792),
-    "deepseek_s": wl.scaled(wl.CONFIGS["deepseek"], d=256, I=192, I_shared=192),
-    "qwen15_s": wl.scaled(wl.CONFIGS["qwen15"], d=256, I=192, I_shared=704),
+    "deepseek_s": wl.scaled(wl.CONFIGS["deepseek"], d=256, I=384, I_shared=128),
+    "qwen15_s": wl.scaled(wl.CONFIGS["qwen15"], d=384, I=128, I_shared=640),
     "qwen3_s": wl.scaled(wl.CONFIGS["qwen3"], d=256, I=128),
 }
 
