@@ -19,7 +19,9 @@
 template <int NT>   // NT = ceil(N / 16) expert tiles
 __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     int T, int d, int N, int k, const uint16_t *__restrict__ h, const uint16_t *__restrict__ gate_w,
-    const float *__restrict__ bias, int norm_mode, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w)
+    const float *__restrict__ bias, int norm_mode, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm)   // non-null counts: single-block launch that also does histogram, scan and permutation
 {
     constexpr int NP = NT * 16;                       // padded expert count
     __shared__ float part[4][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
@@ -103,7 +105,40 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
         if (lane < k) {
             topk_idx[(size_t)t * k + lane] = my_idx;
             topk_w[(size_t)t * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+            if (counts != nullptr) reinterpret_cast<int *>(&part[0][0][0])[tt * k + lane] = my_idx;   // keep for the tail below
         }
+    }
+    if (counts == nullptr) return;
+
+    // ---- decode-sized batch (one block, T*k <= 128): histogram, scan and stable permutation right here ----
+    __shared__ int hist[MOE_MAX_EXPERTS + 1];
+    int *sel_idx = reinterpret_cast<int *>(&part[0][0][0]);      // the partial-logit scratch is free again
+    const int R = T * k;
+    if (threadIdx.x <= MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
+    __syncthreads();
+    int my_e = -1, rank = 0;
+    if ((int)threadIdx.x < R) {
+        my_e = sel_idx[threadIdx.x];
+        atomicAdd(&hist[my_e], 1);
+        for (int r = 0; r < (int)threadIdx.x; ++r) rank += sel_idx[r] == my_e;   // rows of the same expert before this one
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int j = 0; j < N; ++j) {
+            const int c = hist[j];
+            counts[j] = c;
+            offsets[j] = run;
+            hist[j] = run;
+            run += c;
+        }
+        offsets[N] = run;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < R) {
+        const int p = hist[my_e] + rank;
+        perm[p] = threadIdx.x;
+        inv_perm[threadIdx.x] = p;
     }
 }
 
@@ -251,7 +286,8 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const ui
 // ---------------------------------------------------------------------------------------------------
 // host side
 static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_w, const float *bias, int norm_mode,
-                            int32_t *topk_idx, float *topk_w, hipStream_t st)
+                            int32_t *topk_idx, float *topk_w, hipStream_t st, int32_t *counts = nullptr,
+                            int32_t *offsets = nullptr, int32_t *perm = nullptr, int32_t *inv_perm = nullptr)
 {
     const int NT = (s->N + 15) / 16;
     dim3 grid((s->T + ROUTE_TOKENS - 1) / ROUTE_TOKENS), block(ROUTE_THREADS);
@@ -259,7 +295,7 @@ static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_
 #define GT(n)                                                                                                       \
     case n:                                                                                                         \
         hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode, \
-                           topk_idx, topk_w);                                                                       \
+                           topk_idx, topk_w, counts, offsets, perm, inv_perm);                                      \
         break;
     switch (NT) {
         GT(1) GT(2) GT(3) GT(4) GT(5) GT(6) GT(7) GT(8)
@@ -275,6 +311,8 @@ int moe_route_impl(const moe_shape *s, const void *h, const void *gate_w, const 
                    int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
                    int32_t *inv_perm, hipStream_t st)
 {
+    if (s->T <= ROUTE_TOKENS && s->T * s->k <= 128)      // one block: everything in a single launch
+        return launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, counts, offsets, perm, inv_perm);
     int rc = launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st);
     if (rc != MOE_OK) return rc;
     hipLaunchKernelGGL(hist_scan_perm_kernel, dim3(s->N), dim3(256), 0, st, s->T * s->k, s->N, topk_idx, counts,
