@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # flop/s, MI355X dense bf16 matrix peak
 PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
+# HBM bytes per launch of the dominant kernels (fetched + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this script, scaled by what the same counters read for a plain 1 GiB copy (see profiles/)
+TRAFFIC_PREFILL_UP = 2.61e9 + 87.2e6
+TRAFFIC_DECODE_UP = {1: 470.0e6, 16: 1.176e9 + 0.75e6}
 
 
 def log(*a):
@@ -95,6 +99,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=50)
     ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy 5 times (reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -108,6 +114,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.load_library()   # raises if the HIP library has not been built
     torch.cuda.set_device(0)
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] calibration copy done: 5 x (1 GiB read + 1 GiB written)")
+        return
 
     cfg = wl.CONFIGS["mixtral"]
     T = 2048
@@ -133,9 +148,9 @@ def main():
     value = T / (wall / args.steps)
     log(f"[bench] prefill T={T}: {ms_per_step:.3f} ms/step, up {up * 1e3:.3f} ms, ffn {ffn * 1e3:.3f} ms, "
         f"counts={counts.tolist()}, rows_on={rows_on}")
-    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0> (gate/up projection + SwiGLU)",
+    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0,4> (gate/up projection + SwiGLU)",
                 "achieved": up_flops / up / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
-                "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": None,
+                "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": TRAFFIC_PREFILL_UP,
                 "ffn_achieved": ffn_flops / ffn / 1e12, "ffn_frac": ffn_flops / ffn / PEAK_BF16_MFMA,
                 "flops_per_launch": up_flops, "avg_launch_ms": up * 1e3}
 
@@ -158,7 +173,7 @@ def main():
                                         "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": up_bytes / up_d / PEAK_HBM if active else 0.0,
                                         "ffn_frac": ffn_bytes / ffn_d / PEAK_HBM if active else 0.0,
                                         "step_frac": ffn_bytes / (wall_g / args.decode_steps) / PEAK_HBM if active else 0.0,
-                                        "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "traffic": None}})
+                                        "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "traffic": TRAFFIC_DECODE_UP.get(Td)}})
             log(f"[bench] decode T={Td}: graph {decode[-1]['ms_per_step']:.4f} ms/step, eager {decode[-1]['eager_ms_per_step']:.4f}, "
                 f"up {up_d * 1e3:.4f} ms, ffn {ffn_d * 1e3:.4f} ms, active={active}")
 
