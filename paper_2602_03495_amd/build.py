@@ -20,7 +20,7 @@ def build_library(verbose: bool = False) -> str:
            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG, "csrc"),
            # keep hipcc from forming packed-fp32 instructions out of ordinary float code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", LIB] + sources()
+           "-o", LIB] + os.environ.get("MOE_EXTRA_HIPCC_FLAGS", "").split() + sources()
     if verbose:
         cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

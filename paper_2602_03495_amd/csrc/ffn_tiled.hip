@@ -136,7 +136,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
 
     const int nk = kb_n;          // k32 steps (a multiple of 4: K % 128 == 0)
     const int nst = nk / 2;       // k64 stages
-    const int st0 = (int)(((unsigned)nt * 7u + (unsigned)e * 3u) % (unsigned)nst);   // where this item's K ring starts
+    const int st0 = (int)(((unsigned)e * 5u) % (unsigned)nst);   // where this item's K ring starts (per expert: tiles that share rows or weights stay in step)
     u32x4 wr[4][NF];              // W(step) lives in set step % 4, loaded 3 steps ahead
     u32x4 xg[2][2];               // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
     bf16x8 xf[8];

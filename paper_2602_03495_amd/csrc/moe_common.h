@@ -51,6 +51,37 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// ---- 64-lane reductions on the DPP crossbar (VALU speed; __shfl_xor goes through LDS and is ~10x slower per step).
+// Inclusive row scans by 1, 2, 4, 8 leave each 16-lane row's result in its last lane; the four row results are
+// then read with v_readlane, so the value returned is wave-uniform.  The combination order is fixed.
+#define MOE_DPP_SHR(ident, v, n) \
+    __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(ident), __float_as_int(v), 0x110 + (n), 0xF, 0xF, false))
+
+__device__ __forceinline__ float wave_max_dpp(float v)
+{
+    const float ninf = -__builtin_huge_valf();
+    v = fmaxf(v, MOE_DPP_SHR(ninf, v, 1));
+    v = fmaxf(v, MOE_DPP_SHR(ninf, v, 2));
+    v = fmaxf(v, MOE_DPP_SHR(ninf, v, 4));
+    v = fmaxf(v, MOE_DPP_SHR(ninf, v, 8));
+    const int b = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 15)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 31));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 47)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 63));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v += MOE_DPP_SHR(0.f, v, 1);
+    v += MOE_DPP_SHR(0.f, v, 2);
+    v += MOE_DPP_SHR(0.f, v, 4);
+    v += MOE_DPP_SHR(0.f, v, 8);
+    const int b = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 15)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 31));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 47)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 63));
+    return (r0 + r1) + (r2 + r3);
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
 #define MOE_CHECK_LAUNCH()                       \

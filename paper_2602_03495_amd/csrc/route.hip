@@ -2,8 +2,8 @@
 //
 // moe_route (Eq. 1 and the expert workload of Section "Greedy Assignment Strategy"):
 //   gate_topk_kernel      16 tokens per block; logits by bf16 MFMA 16x16x32 straight from global memory
-//                         (K split over the 4 waves, reduced through LDS), then softmax and top-k per token
-//                         inside one wavefront with xor-shuffle arg-max rounds.
+//                         (K split over the 8 waves, reduced through LDS), then softmax and top-k per token
+//                         inside one wavefront: k rounds of a DPP max reduction + ballot.
 //   hist_scan_perm_kernel one block per expert: LDS-staged histogram of all selections (LDS atomics),
 //                         exclusive scan, and a ballot-based stable compaction of that expert's rows.
 // moe_predict_workload (Section "Residual-Based Prefetching"):
@@ -13,7 +13,8 @@
 #include "moe_common.h"
 
 #define ROUTE_TOKENS 16      // tokens per block of gate_topk_kernel
-#define ROUTE_THREADS 256
+#define ROUTE_THREADS 512
+#define ROUTE_WAVES 8
 
 // ---------------------------------------------------------------------------------------------------
 template <int NT>   // NT = ceil(N / 16) expert tiles
@@ -24,8 +25,8 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     int32_t *__restrict__ inv_perm)   // non-null counts: single-block launch that also does histogram, scan and permutation
 {
     constexpr int NP = NT * 16;                       // padded expert count
-    __shared__ float part[4][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
-    __shared__ float lg[ROUTE_TOKENS][NP + 1];        // reduced logits (+bias)
+    __shared__ float part[ROUTE_WAVES][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
+    __shared__ __attribute__((aligned(16))) float lg[ROUTE_TOKENS][NP + 4];   // reduced logits (+bias), rows 16-byte aligned
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -47,12 +48,30 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // K is dealt to the 8 waves in 32-wide steps (step s -> wave s % 8); each wave issues the loads of four of
+    // its steps before the first MFMA so that the block has ~8 x 4 x (1 + NT) loads in flight
     const int nsteps = d >> 5;
-    for (int s = wave; s < nsteps; s += 4) {
-        bf16x8 a = as_frag(*reinterpret_cast<const uint4 *>(hp + s * 32));
+    int s = wave;
+    for (; s + 3 * ROUTE_WAVES < nsteps; s += 4 * ROUTE_WAVES) {
+        u32x4 a[4], b[4][NT];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = *reinterpret_cast<const u32x4 *>(hp + (s + u * ROUTE_WAVES) * 32);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) b[u][nt] = *reinterpret_cast<const u32x4 *>(wp[nt] + (s + u * ROUTE_WAVES) * 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep every load of the batch ahead of the first MFMA
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[u]), as_frag(b[u][nt]), acc[nt], 0, 0, 0);
+    }
+    for (; s < nsteps; s += ROUTE_WAVES) {
+        bf16x8 a = as_frag(*reinterpret_cast<const u32x4 *>(hp + s * 32));
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            bf16x8 b = as_frag(*reinterpret_cast<const uint4 *>(wp[nt] + s * 32));
+            bf16x8 b = as_frag(*reinterpret_cast<const u32x4 *>(wp[nt] + s * 32));
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
         }
     }
@@ -64,44 +83,49 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     __syncthreads();
     for (int idx = threadIdx.x; idx < ROUTE_TOKENS * NP; idx += ROUTE_THREADS) {
         int tt = idx / NP, e = idx % NP;
-        float v = (part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e]);
+        float v = ((part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e])) +
+                  ((part[4][tt][e] + part[5][tt][e]) + (part[6][tt][e] + part[7][tt][e]));
         if (bias != nullptr && e < N) v += bias[e];
         lg[tt][e] = v;
     }
     __syncthreads();
 
-    // ---- softmax + top-k: one wave per token, lane l owns experts l and l+64 ---------------------
-    for (int q = 0; q < ROUTE_TOKENS / 4; ++q) {
-        const int tt = wave * (ROUTE_TOKENS / 4) + q;
+    // ---- softmax + top-k: one wave per token, lane l owns experts l and l+64.  k rounds of: wave-wide max on the
+    // DPP crossbar, then the lowest expert index holding that value (ballot + find-first-set; the lower 64 experts
+    // are asked first), which is the tie rule "equal scores by ascending index".
+    for (int q = 0; q < ROUTE_TOKENS / ROUTE_WAVES; ++q) {
+        const int tt = wave * (ROUTE_TOKENS / ROUTE_WAVES) + q;
         const int t = t0 + tt;
         if (t >= T) break;                                   // uniform per wave
         const float NEG = -__builtin_huge_valf();
         float v0 = lane < N ? lg[tt][lane] : NEG;
         float v1 = (NT > 4 && lane + 64 < N) ? lg[tt][lane + 64] : NEG;
-        float m = fmaxf(v0, v1);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, MOE_WAVE));
-        float p0 = lane < N ? expf(v0 - m) : 0.f;
-        float p1 = (NT > 4 && lane + 64 < N) ? expf(v1 - m) : 0.f;
-        const float den = wave_sum(p0 + p1);
+        const float m = wave_max_dpp(fmaxf(v0, v1));
+        const float p0 = lane < N ? expf(v0 - m) : 0.f;
+        const float p1 = (NT > 4 && lane + 64 < N) ? expf(v1 - m) : 0.f;
+        const float den = wave_sum_dpp(p0 + p1);
 
         int my_idx = 0;
-        float my_p = 0.f;
+        float my_p = 0.f, sel = 0.f;
+        float best = m;
         for (int s = 0; s < k; ++s) {
-            float bv;
+            if (s > 0) best = wave_max_dpp(fmaxf(v0, v1));
+            const unsigned long long b0 = __ballot(v0 == best);
+            const unsigned long long b1 = __ballot(v1 == best);
             int bi;
-            if (v0 >= v1) { bv = v0; bi = lane; } else { bv = v1; bi = lane + 64; }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                float ov = __shfl_xor(bv, o, MOE_WAVE);
-                int oi = __shfl_xor(bi, o, MOE_WAVE);
-                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            if (b0 != 0ull) {
+                bi = __ffsll((long long)b0) - 1;
+                if (lane == bi) v0 = NEG;
+            } else if (b1 != 0ull) {
+                bi = __ffsll((long long)b1) - 1 + 64;
+                if (lane + 64 == bi) v1 = NEG;
+            } else {
+                bi = N - 1;                                  // only reachable with NaN logits: stay in range
             }
-            if (bi == lane) v0 = NEG;
-            if (bi == lane + 64) v1 = NEG;
-            if (lane == s) { my_idx = bi < N ? bi : N - 1; my_p = expf(bv - m) / den; }   // (NaN logits cannot index out of range)
+            const float pb = expf(best - m) / den;           // uniform
+            sel += pb;
+            if (lane == s) { my_idx = bi; my_p = pb; }
         }
-        float sel = wave_sum(lane < k ? my_p : 0.f);
         if (lane < k) {
             topk_idx[(size_t)t * k + lane] = my_idx;
             topk_w[(size_t)t * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
@@ -143,63 +167,89 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------------
-// One block per expert.  Every block histograms all R selections in LDS (cheap, and it spares a global
-// zero-fill and cross-block atomics), scans the N counts, and then places the rows of its own expert in
-// ascending r, so the permutation is stable and the same on every run.
+// One block per expert e.  Pass 1 counts, in registers, the selections that are below e and equal to e (their
+// block-wide sums are offsets[e] and counts[e]: no global zero-fill, no cross-block atomics, no shared bins to
+// fight over); pass 2 places the rows of expert e in ascending r with wave ballots, so the permutation is stable
+// and the same on every run.  Selections are read 16 K at a time, 64 per thread, all loads in flight at once;
+// when T*k <= 16 K both passes work from the same registers.
+#define HSP_PER_THREAD 64
+#define HSP_SUPER (256 * HSP_PER_THREAD)
 __global__ __launch_bounds__(256) void hist_scan_perm_kernel(
     int R, int N, const int32_t *__restrict__ topk_idx, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm)
 {
-    __shared__ int hist[MOE_MAX_EXPERTS];
-    __shared__ int wave_tot[4];
+    __shared__ int red[2][4];
+    __shared__ int wave_tot[HSP_PER_THREAD / 4][4];
     __shared__ int my_off;
     const int e = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    if (threadIdx.x < MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
-    __syncthreads();
-    for (int r = threadIdx.x; r < R; r += 256) atomicAdd(&hist[topk_idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
+    // entry j of this thread in super-chunk c0: r = c0 + (j/4)*1024 + wave*256 + (j%4)*64 + lane
+    int v[HSP_PER_THREAD];
+    auto load_super = [&](int c0) {
+#pragma unroll
+        for (int j = 0; j < HSP_PER_THREAD; ++j) {
+            const int r = c0 + (j >> 2) * 1024 + wave * 256 + (j & 3) * 64 + lane;
+            v[j] = r < R ? topk_idx[r] : -1;
+        }
+    };
+    int below = 0, equal = 0;
+    for (int c0 = 0; c0 < R; c0 += HSP_SUPER) {
+        load_super(c0);
+#pragma unroll
+        for (int j = 0; j < HSP_PER_THREAD; ++j) {
+            below += (unsigned)v[j] < (unsigned)e;          // padding entries are -1 = huge unsigned
+            equal += v[j] == e;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        below += __shfl_xor(below, o, MOE_WAVE);
+        equal += __shfl_xor(equal, o, MOE_WAVE);
+    }
+    if (lane == 0) { red[0][wave] = below; red[1][wave] = equal; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int run = 0;
-        for (int j = 0; j < N; ++j) {
-            int c = hist[j];
-            if (j == e) my_off = run;
-            if (e == 0) { counts[j] = c; offsets[j] = run; }
-            run += c;
-        }
-        if (e == 0) offsets[N] = run;
+        const int off = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        const int cnt = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+        my_off = off;
+        counts[e] = cnt;
+        offsets[e] = off;
+        if (e == N - 1) offsets[N] = off + cnt;
     }
     __syncthreads();
     int base = my_off;                                      // running output position, uniform
-    for (int c0 = 0; c0 < R; c0 += 1024) {
-        int r[4];
-        bool hit[4];
-        unsigned long long bal[4];
-        int tot = 0;
+    const unsigned long long lower = (1ull << lane) - 1ull;
+    for (int c0 = 0; c0 < R; c0 += HSP_SUPER) {
+        if (R > HSP_SUPER) load_super(c0);                  // otherwise v[] still holds the only super-chunk
+        unsigned long long bal[HSP_PER_THREAD];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            r[j] = c0 + wave * 256 + j * 64 + lane;
-            hit[j] = r[j] < R && topk_idx[r[j]] == e;
-            bal[j] = __ballot(hit[j]);
-            tot += __popcll(bal[j]);
-        }
-        if (lane == 0) wave_tot[wave] = tot;
-        __syncthreads();
-        int pos = base;
-        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
-        const int chunk_tot = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
-        const unsigned long long lower = (1ull << lane) - 1ull;
+        for (int c = 0; c < HSP_PER_THREAD / 4; ++c) {
+            int tot = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (hit[j]) {
-                int p = pos + __popcll(bal[j] & lower);
-                perm[p] = r[j];
-                inv_perm[r[j]] = p;
+            for (int j = 0; j < 4; ++j) {
+                bal[4 * c + j] = __ballot(v[4 * c + j] == e);
+                tot += __popcll(bal[4 * c + j]);
             }
-            pos += __popcll(bal[j]);
+            if (lane == 0) wave_tot[c][wave] = tot;
         }
-        base += chunk_tot;
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < HSP_PER_THREAD / 4; ++c) {
+            int pos = base;
+            for (int w = 0; w < wave; ++w) pos += wave_tot[c][w];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (v[4 * c + j] == e) {
+                    const int r = c0 + c * 1024 + wave * 256 + j * 64 + lane;
+                    const int p = pos + __popcll(bal[4 * c + j] & lower);
+                    perm[p] = r;
+                    inv_perm[r] = p;
+                }
+                pos += __popcll(bal[4 * c + j]);
+            }
+            base += wave_tot[c][0] + wave_tot[c][1] + wave_tot[c][2] + wave_tot[c][3];
+        }
         __syncthreads();
     }
 }
