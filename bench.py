@@ -99,6 +99,11 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=50)
     ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--stack", action="store_true",
+                    help="run the Qwen3-30B-A3B-shaped decode stack instead (48 layers, 256 steps, batch 16, AR(1) routing) "
+                         "and print its own JSON line: per-step workload histograms, prediction accuracy, tokens/s")
+    ap.add_argument("--stack-layers", type=int, default=48)
+    ap.add_argument("--stack-steps", type=int, default=256)
     ap.add_argument("--calib-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy 5 times (reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -122,6 +127,29 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log("[bench] calibration copy done: 5 x (1 GiB read + 1 GiB written)")
+        return
+
+    if args.stack:
+        from paper_2602_03495_amd.stack import DecodeStack
+        cfg5 = wl.CONFIGS["qwen3"]
+        t0 = time.time()
+        st = DecodeStack(cfg5, args.stack_layers, 16)
+        log(f"[bench] stack: {args.stack_layers} layers resident ({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.0f}s")
+        bias = st.bias_paths(args.stack_steps)
+        st.calibrate(bias)
+        res = st.run(args.stack_steps, bias, use_res_vec=True)
+        raw = st.run(min(args.stack_steps, 64), bias, use_res_vec=False)
+        c = res.counts
+        hist = {"shape": list(c.shape), "max_workload": int(c.max()), "mean_active_experts": float((c > 0).sum(-1).mean()),
+                "mean_top1_share": float((c.max(-1) / c.sum(-1)).mean()),
+                "first_step_first_layer": c[0, 0].tolist()}
+        out = {"metric": "decode-stack tokens/sec (48 layers x 256 steps, batch 16)", "value": res.tokens_per_s, "unit": "tokens/s",
+               "n_gpus": 1, "steps": args.stack_steps, "layers": args.stack_layers, "ms_per_step": res.seconds / args.stack_steps * 1e3,
+               "us_per_layer": res.seconds / args.stack_steps / args.stack_layers * 1e6, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": "qwen3-30b-a3b-shaped decode stack, AR(1) gate bias rho=0.9, mask = top half by previous step"},
+               "prediction_accuracy_with_res_vec": res.acc, "prediction_accuracy_without_res_vec": raw.acc,
+               "histograms": hist}
+        print(json.dumps(out), flush=True)
         return
 
     cfg = wl.CONFIGS["mixtral"]

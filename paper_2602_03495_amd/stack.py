@@ -1,0 +1,116 @@
+"""Decode run over a stack of MoE layers with temporally correlated routing (the Qwen3-30B-A3B-shaped workload):
+every step feeds a fresh batch through all layers, each layer's gate bias follows an AR(1) path around its Zipf
+mean, the expert mask of a layer is the top half of that layer's previous-step workloads, and the next layer's
+workload is predicted from the current features plus a calibrated residual vector.
+
+Plumbing only: the layer arithmetic runs in the library's kernels; the glue between layers -- the residual
+connection followed by an RMS normalisation, h <- rmsnorm(h + MoE(h)), which keeps the synthetic stream at unit
+scale over 48 layers the way a transformer block's norm does -- and the bookkeeping of histograms are done with
+torch tensor ops, outside the timed calls.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import layer as Lm
+from . import workloads as wl
+
+
+@dataclass
+class StackResult:
+    counts: np.ndarray            # [steps, layers, N] actual workloads
+    pred_counts: np.ndarray       # [steps, layers-1, N] predicted workloads of layer l+1 made at layer l
+    seconds: float                # GPU time of the timed calls (route + predict + ffn + combine), all steps
+    tokens_per_s: float
+    acc: dict = field(default_factory=dict)   # p -> mean |pred_top_p & true_top_p| / p (tie tolerant)
+
+
+def next_hidden(h: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """Gate input of the next layer: residual connection, then RMS normalisation per token."""
+    x = h.float() + out.float()
+    x = x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + 1e-6)
+    return x.to(torch.bfloat16)
+
+
+def top_p_accuracy(pred: np.ndarray, true: np.ndarray, p: int) -> float:
+    """Share of the p predicted experts whose true workload reaches the p-th largest true workload."""
+    order = np.lexsort((np.arange(pred.size), -pred.astype(np.int64)))[:p]
+    kth = np.sort(true)[::-1][p - 1]
+    return float(np.mean(true[order] >= kth))
+
+
+class DecodeStack:
+    def __init__(self, cfg: wl.LayerConfig, n_layers: int, T: int = 16, device="cuda"):
+        self.cfg, self.n_layers, self.T = cfg, n_layers, T
+        self.weights: List[Lm.LayerWeights] = []
+        for l in range(n_layers):
+            w1, w3, w2 = wl.expert_weights(cfg, l)
+            self.weights.append(Lm.LayerWeights.upload(wl.gate_weights(cfg, l), wl.gate_bias(cfg, l), w1, w3, w2))
+        self.layer = Lm.MoeLayer(cfg, T)
+        self.res_vec = [torch.zeros(cfg.d, dtype=torch.float32, device=device) for _ in range(n_layers)]
+        self.top = torch.empty(8, dtype=torch.int32, device=device)
+
+    def bias_paths(self, steps: int) -> torch.Tensor:
+        """[layers, steps, N] fp32 AR(1) gate-bias paths, on the device."""
+        b = np.stack([wl.ar1_bias_path(self.cfg, l, steps) for l in range(self.n_layers)])
+        return torch.from_numpy(b).cuda()
+
+    def calibrate(self, bias: torch.Tensor, steps: int = 4):
+        """res_vec^(l) = mean over calibration tokens of h^(l+1) - h^(l) (the paper's res_vec equation), from
+        `steps` batches that are not part of the measured run."""
+        cfg, L = self.cfg, self.layer
+        acc = [torch.zeros(cfg.d, dtype=torch.float64, device="cuda") for _ in range(self.n_layers)]
+        for t in range(steps):
+            h = Lm.to_device_bf16(wl.hidden_states(cfg, self.T, draw=100000 + t))
+            for l in range(self.n_layers):
+                out = L.forward(h, self.weights[l], None, bias=bias[l, t % bias.shape[1]].contiguous())
+                h_next = next_hidden(h, out)
+                acc[l] += (h_next.double() - h.double()).sum(0)
+                h = h_next
+        for l in range(self.n_layers):
+            self.res_vec[l] = (acc[l] / (steps * self.T)).float()
+
+    def run(self, steps: int, bias: torch.Tensor, use_res_vec: bool = True, p_list=(1, 4, 8)) -> StackResult:
+        cfg, L, nl = self.cfg, self.layer, self.n_layers
+        counts = torch.zeros((steps, nl, cfg.N), dtype=torch.int32, device="cuda")
+        preds = torch.zeros((steps, max(nl - 1, 1), cfg.N), dtype=torch.int32, device="cuda")
+        masks = [torch.ones(cfg.N, dtype=torch.uint8, device="cuda") for _ in range(nl)]
+        zero_rv = torch.zeros(cfg.d, dtype=torch.float32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        total_ms = 0.0
+        for t in range(steps):
+            h = Lm.to_device_bf16(wl.hidden_states(cfg, self.T, draw=t))
+            for l in range(nl):
+                w = self.weights[l]
+                b = bias[l, t].contiguous()
+                e0.record()
+                L.route(h, w, b)
+                if l + 1 < nl:
+                    L.predict(h, self.res_vec[l] if use_res_vec else zero_rv, self.weights[l + 1], 8, self.top,
+                              next_bias=bias[l + 1, t].contiguous())
+                L.expert_ffn(h, w, masks[l])
+                out = L.combine(masks[l])
+                e1.record()
+                e1.synchronize()
+                total_ms += e0.elapsed_time(e1)
+                counts[t, l] = L.routing.counts
+                if l + 1 < nl:
+                    preds[t, l] = L.pred_counts
+                # next step's mask of this layer: the half of the experts with the largest workloads now
+                order = torch.sort(L.routing.counts.to(torch.int64) * cfg.N + (cfg.N - 1 - torch.arange(cfg.N, device="cuda")),
+                                   descending=True).indices
+                m = torch.zeros(cfg.N, dtype=torch.uint8, device="cuda")
+                m[order[: cfg.N // 2]] = 1
+                masks[l] = m
+                h = next_hidden(h, out)
+        c, pr = counts.cpu().numpy(), preds.cpu().numpy()
+        res = StackResult(c, pr, total_ms * 1e-3, self.T * steps / (total_ms * 1e-3))
+        for p in p_list:
+            if nl > 1:
+                res.acc[p] = float(np.mean([top_p_accuracy(pr[t, l], c[t, l + 1], p) for t in range(steps) for l in range(nl - 1)]))
+        return res
