@@ -182,6 +182,40 @@ int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32
  */
 int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *scale, void *stream);
 
+/* ------------------------------------------------------------------------------------------------------------
+ * Host-side scheduling policies fed by the workload histograms (all pointers [host]; nothing touches the GPU).
+ * ------------------------------------------------------------------------------------------------------------ */
+
+/*
+ * Expected execution time of every expert on either side (Section "Greedy Assignment Strategy"):
+ *   t_cpu[e] = cpu_compute[min(counts[e], wmax)],
+ *   t_gpu[e] = max(Trans, gpu_compute[min(counts[e], wmax)]),  Trans = 0 if cached[e] else trans_time,
+ * and both are 0 for counts[e] = 0 (not activated).  gpu_compute, cpu_compute: [wmax+1] profiled time tables
+ * indexed by workload; cached [N] uint8 or NULL (nothing cached).
+ */
+int moe_expert_times(int N, const int32_t *counts, const uint8_t *cached, float trans_time, const float *gpu_compute,
+                     const float *cpu_compute, int wmax, float *t_gpu, float *t_cpu);
+
+/*
+ * Greedy Assignment (Alg. 1): visit the experts in descending |t_gpu - t_cpu| (equal differences by ascending
+ * index) and give each to the side with the smaller running total after adding it (the GPU when equal); experts
+ * with t_gpu = t_cpu = 0 stay unassigned.  G, C: [N] uint8 outputs (G is the expert_mask of moe_expert_ffn);
+ * T_gpu, T_cpu: the two totals (may be NULL).  The GPU-memory constraint is not checked, as in the algorithm.
+ */
+int moe_greedy_assign(int N, const float *t_gpu, const float *t_cpu, uint8_t *G, uint8_t *C, float *T_gpu, float *T_cpu);
+
+/*
+ * Workload-Aware Cache Replacement (Alg. 2), one token step of one layer.  score [N] int64 and on_gpu [N] uint8
+ * are the persistent state (start with score = 0, *step_in_window = 0 and the initial cache in on_gpu).
+ * workload [N] is this step's expert workload (summed over the sequences of the batch).  After every w_size steps
+ * the u_size highest-score experts off the GPU replace the u_size lowest-score experts on it -- the text's reading
+ * of the algorithm's second TopK -- pairwise, best incoming against worst outgoing, stopping at the first pair
+ * whose incoming score is not larger; then the scores are reset.  evicted / loaded [u_size] receive the swapped
+ * ids, *n_swapped their number (0 on steps that do not close a window).
+ */
+int moe_cache_step(int N, int w_size, int u_size, const int32_t *workload, int64_t *score, uint8_t *on_gpu,
+                   int32_t *step_in_window, int32_t *evicted, int32_t *loaded, int32_t *n_swapped);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,8 @@ FFN_AUTO, FFN_TILED, FFN_SKINNY = 0, 1, 2
 NORM_NONE, NORM_RENORM = 0, 1
 
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
-           "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights"]
+           "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
+           "moe_expert_times", "moe_greedy_assign", "moe_cache_step"]
 
 
 class MoeShape(C.Structure):
