@@ -163,6 +163,45 @@ def moe_pack_weights(src: torch.Tensor, dst: Optional[torch.Tensor] = None) -> t
     return dst
 
 
+def greedy_assign(t_gpu, t_cpu):
+    """Alg. 1 on host arrays: returns (G, C, T_gpu, T_cpu) with G, C as uint8 numpy arrays."""
+    import numpy as np
+    tg, tc = np.ascontiguousarray(t_gpu, np.float32), np.ascontiguousarray(t_cpu, np.float32)
+    N = tg.size
+    G, Cc = np.zeros(N, np.uint8), np.zeros(N, np.uint8)
+    Tg, Tc = C.c_float(0), C.c_float(0)
+    f, b = C.POINTER(C.c_float), C.POINTER(C.c_uint8)
+    _check(load_library().moe_greedy_assign(C.c_int(N), tg.ctypes.data_as(f), tc.ctypes.data_as(f), G.ctypes.data_as(b),
+                                            Cc.ctypes.data_as(b), C.byref(Tg), C.byref(Tc)), "moe_greedy_assign")
+    return G, Cc, Tg.value, Tc.value
+
+
+class ExpertCache:
+    """Alg. 2 state of one layer, advanced by moe_cache_step."""
+
+    def __init__(self, N: int, on_gpu_ids, w_size: int, u_size: int):
+        import numpy as np
+        self.N, self.w_size, self.u_size = N, w_size, u_size
+        self.score = np.zeros(N, np.int64)
+        self.on_gpu = np.zeros(N, np.uint8)
+        self.on_gpu[list(on_gpu_ids)] = 1
+        self.step_in_window = C.c_int32(0)
+        self._ev = np.full(max(u_size, 1), -1, np.int32)
+        self._ld = np.full(max(u_size, 1), -1, np.int32)
+
+    def step(self, workload):
+        import numpy as np
+        w = np.ascontiguousarray(workload, np.int32)
+        n = C.c_int32(0)
+        i32, i64, u8 = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+        _check(load_library().moe_cache_step(C.c_int(self.N), C.c_int(self.w_size), C.c_int(self.u_size),
+                                             w.ctypes.data_as(i32), self.score.ctypes.data_as(i64),
+                                             self.on_gpu.ctypes.data_as(u8), C.byref(self.step_in_window),
+                                             self._ev.ctypes.data_as(i32), self._ld.ctypes.data_as(i32), C.byref(n)),
+               "moe_cache_step")
+        return [(int(self._ev[j]), int(self._ld[j])) for j in range(n.value)]
+
+
 def moe_dense_route(s: MoeShape, counts, offsets, perm):
     rc = load_library().moe_dense_route(C.byref(s), _ptr(counts, torch.int32), _ptr(offsets, torch.int32),
                                         _ptr(perm, torch.int32), _stream())
