@@ -2,7 +2,7 @@
 #include "moe_common.h"
 
 int moe_route_impl(const moe_shape *, const void *, const void *, const float *, int, int32_t *, float *, int32_t *,
-                   int32_t *, int32_t *, int32_t *, hipStream_t);
+                   int32_t *, int32_t *, int32_t *, void *, hipStream_t);
 int moe_predict_impl(const moe_shape *, const void *, const float *, const void *, const float *, int, int32_t *,
                      int32_t *, void *, hipStream_t);
 int moe_dense_route_impl(const moe_shape *, int32_t *, int32_t *, int32_t *, hipStream_t);
@@ -62,8 +62,9 @@ int moe_route(const moe_shape *s, const void *h, const void *gate_w, const float
     if (!h || !gate_w || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_EINVAL;
     if (!aligned16(h) || !aligned16(gate_w)) return MOE_EINVAL;
     if (norm_mode != MOE_NORM_NONE && norm_mode != MOE_NORM_RENORM) return MOE_EINVAL;
-    (void)workspace;
-    return moe_route_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm,
+    if (workspace != nullptr && ((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    if (workspace != nullptr && (s->I < 128 || s->I % 128 != 0)) return MOE_EINVAL;    // the workspace layout depends on I
+    return moe_route_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace,
                           (hipStream_t)stream);
 }
 

@@ -22,7 +22,9 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     int T, int d, int N, int k, const uint16_t *__restrict__ h, const uint16_t *__restrict__ gate_w,
     const float *__restrict__ bias, int norm_mode, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv_perm)   // non-null counts: single-block launch that also does histogram, scan and permutation
+    int32_t *__restrict__ inv_perm,   // non-null counts: single-block launch that also does histogram, scan and permutation
+    const float *__restrict__ logits_in,   // non-null: skip the gate product, select from these [T,N] logits
+    float *__restrict__ logits_out)        // non-null: only compute logits of experts 16*NT*blockIdx.y .. and store them [T,N]
 {
     constexpr int NP = NT * 16;                       // padded expert count
     __shared__ float part[ROUTE_WAVES][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
@@ -32,6 +34,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     const int wave = threadIdx.x >> 6;
     const int t0 = blockIdx.x * ROUTE_TOKENS;
     const int i = lane & 15, g = lane >> 4;
+    const int e_base = logits_out != nullptr ? blockIdx.y * NP : 0;   // first expert of this block
 
     // ---- logits: D[token][expert] += A[token][k] * B[k][expert], 32 k per MFMA -------------------
     int tr = t0 + i;
@@ -40,7 +43,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     const uint16_t *wp[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        int er = nt * 16 + i;
+        int er = e_base + nt * 16 + i;
         if (er >= N) er = N - 1;
         wp[nt] = gate_w + (size_t)er * d + g * 8;
     }
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
 
     // K is dealt to the 8 waves in 32-wide steps (step s -> wave s % 8); each wave issues the loads of four of
     // its steps before the first MFMA so that the block has ~8 x 4 x (1 + NT) loads in flight
-    const int nsteps = d >> 5;
+    const int nsteps = logits_in != nullptr ? 0 : d >> 5;
     int s = wave;
     for (; s + 3 * ROUTE_WAVES < nsteps; s += 4 * ROUTE_WAVES) {
         u32x4 a[4], b[4][NT];
@@ -85,9 +88,18 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
         int tt = idx / NP, e = idx % NP;
         float v = ((part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e])) +
                   ((part[4][tt][e] + part[5][tt][e]) + (part[6][tt][e] + part[7][tt][e]));
-        if (bias != nullptr && e < N) v += bias[e];
-        lg[tt][e] = v;
+        if (logits_in != nullptr) {
+            v = (t0 + tt < T && e < N) ? logits_in[(size_t)(t0 + tt) * N + e] : 0.f;
+        } else if (bias != nullptr && e_base + e < N) {
+            v += bias[e_base + e];
+        }
+        if (logits_out != nullptr) {
+            if (t0 + tt < T && e_base + e < N) logits_out[(size_t)(t0 + tt) * N + e_base + e] = v;
+        } else {
+            lg[tt][e] = v;
+        }
     }
+    if (logits_out != nullptr) return;
     __syncthreads();
 
     // ---- softmax + top-k: one wave per token, lane l owns experts l and l+64.  k rounds of: wave-wide max on the
@@ -336,16 +348,26 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const ui
 // ---------------------------------------------------------------------------------------------------
 // host side
 static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_w, const float *bias, int norm_mode,
-                            int32_t *topk_idx, float *topk_w, hipStream_t st, int32_t *counts = nullptr,
+                            int32_t *topk_idx, float *topk_w, hipStream_t st, float *ws_logits, int32_t *counts = nullptr,
                             int32_t *offsets = nullptr, int32_t *perm = nullptr, int32_t *inv_perm = nullptr)
 {
     const int NT = (s->N + 15) / 16;
     dim3 grid((s->T + ROUTE_TOKENS - 1) / ROUTE_TOKENS), block(ROUTE_THREADS);
     const uint16_t *hp = (const uint16_t *)h, *wp = (const uint16_t *)gate_w;
+    const float *lin = nullptr;
+    if (s->T <= ROUTE_TOKENS && NT >= 2 && ws_logits != nullptr) {
+        // decode-sized batch with many experts: one block would stream the whole gate matrix alone, so the gate
+        // product is spread over one block per 16 experts and the selection runs from the stored logits
+        hipLaunchKernelGGL(gate_topk_kernel<1>, dim3(1, NT), block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode,
+                           (int32_t *)nullptr, (float *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
+                           (int32_t *)nullptr, (const float *)nullptr, ws_logits);
+        MOE_CHECK_LAUNCH();
+        lin = ws_logits;
+    }
 #define GT(n)                                                                                                       \
     case n:                                                                                                         \
         hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode, \
-                           topk_idx, topk_w, counts, offsets, perm, inv_perm);                                      \
+                           topk_idx, topk_w, counts, offsets, perm, inv_perm, lin, (float *)nullptr);               \
         break;
     switch (NT) {
         GT(1) GT(2) GT(3) GT(4) GT(5) GT(6) GT(7) GT(8)
@@ -357,13 +379,21 @@ static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_
     return MOE_OK;
 }
 
+static float *route_logits_scratch(const moe_shape *s, void *workspace)
+{
+    if (workspace == nullptr) return nullptr;
+    moe_ws_layout L = moe_ws(s);
+    return (float *)((char *)workspace + L.route + moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256((size_t)s->T * s->k * 4));
+}
+
 int moe_route_impl(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
                    int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
-                   int32_t *inv_perm, hipStream_t st)
+                   int32_t *inv_perm, void *workspace, hipStream_t st)
 {
+    float *wl = route_logits_scratch(s, workspace);
     if (s->T <= ROUTE_TOKENS && s->T * s->k <= 128)      // one block: everything in a single launch
-        return launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, counts, offsets, perm, inv_perm);
-    int rc = launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st);
+        return launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, wl, counts, offsets, perm, inv_perm);
+    int rc = launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, wl);
     if (rc != MOE_OK) return rc;
     hipLaunchKernelGGL(hist_scan_perm_kernel, dim3(s->N), dim3(256), 0, st, s->T * s->k, s->N, topk_idx, counts,
                        offsets, perm, inv_perm);
@@ -384,7 +414,7 @@ int moe_predict_impl(const moe_shape *s, const void *h, const float *res_vec, co
     hipLaunchKernelGGL(fold_residual_kernel, dim3(s->N), dim3(64), 0, st, s->d, res_vec, (const uint16_t *)next_gate_w,
                        next_gate_bias, bias2);
     MOE_CHECK_LAUNCH();
-    int rc = launch_gate_topk(s, h, next_gate_w, bias2, MOE_NORM_NONE, idx, w, st);
+    int rc = launch_gate_topk(s, h, next_gate_w, bias2, MOE_NORM_NONE, idx, w, st, route_logits_scratch(s, workspace));
     if (rc != MOE_OK) return rc;
     hipLaunchKernelGGL(hist_top_kernel, dim3(1), dim3(256), 0, st, (int)R, s->N, p, idx, pred_counts, top_experts);
     MOE_CHECK_LAUNCH();
