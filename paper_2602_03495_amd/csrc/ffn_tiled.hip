@@ -62,7 +62,7 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
 // Weight tile of a block: 8 waves x NF fragments x 16 rows.
-template <int MODE, int NF>
+template <int MODE, int NF, int NTT = 8>
 __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
@@ -114,9 +114,10 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     }
     // ---- token tile loader: thread -> rows tid/8 + 64 j (j < 2), 16-byte chunk tid%8 of the 128-byte k64 segment
     const int xc = tid & 7;
-    uint32_t xo[2];
+    constexpr int XJ = NTT > 4 ? 2 : 1;                    // 64-row halves of the token tile that are in use
+    uint32_t xo[XJ];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < XJ; ++j) {
         int r = (tid >> 3) + 64 * j;
         if (r >= nrows) r = nrows - 1;
         if (MODE == 0)
@@ -128,18 +129,18 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     uint16_t *xw = &Xs[0][xc >> 2][(tid >> 3) * 32 + (xc & 3) * 8];   // + buffer * 2*TM*32 + j * 64 rows
     const uint16_t *xrd = &Xs[0][0][li * 32 + lg * 8];               // + buffer * 2*TM*32 + half * TM*32 + t * 16 rows
 
-    f32x4 acc[NF][8];
+    f32x4 acc[NF][NTT];
 #pragma unroll
     for (int f = 0; f < NF; ++f)
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc[f][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NTT; ++t) acc[f][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nk = kb_n;          // k32 steps (a multiple of 4: K % 128 == 0)
     const int nst = nk / 2;       // k64 stages
     const int st0 = (int)(((unsigned)e * 5u) % (unsigned)nst);   // where this item's K ring starts (per expert: tiles that share rows or weights stay in step)
     u32x4 wr[4][NF];              // W(step) lives in set step % 4, loaded 3 steps ahead
-    u32x4 xg[2][2];               // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
-    bf16x8 xf[8];
+    u32x4 xg[2][XJ];              // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
+    bf16x8 xf[NTT];
 
 #define KSTEP(s) (((s) + 2 * st0) % nk)
 #define KSTAGE(st) (((st) + st0) % nst)
@@ -154,23 +155,23 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
 #define XLOAD(set, st)                                                                           \
     do {                                                                                         \
         const size_t ko_ = (size_t)KSTAGE(st) * 64;                                              \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                            \
+        _Pragma("unroll") for (int j = 0; j < XJ; ++j)                                           \
             xg[set][j] = *reinterpret_cast<const u32x4 *>(xbase + xo[j] + ko_);                  \
     } while (0)
 #define XSTORE(buf)                                                                              \
     do {                                                                                         \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                            \
+        _Pragma("unroll") for (int j = 0; j < XJ; ++j)                                           \
             *reinterpret_cast<u32x4 *>(xw + (buf) * (2 * TM * 32) + j * (64 * 32)) = xg[buf][j]; \
     } while (0)
 #define XREAD(buf, half)                                                                         \
     do {                                                                                         \
-        _Pragma("unroll") for (int t = 0; t < 8; ++t)                                            \
+        _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                          \
             xf[t] = as_frag(*reinterpret_cast<const u32x4 *>(xrd + (buf) * (2 * TM * 32) + (half) * (TM * 32) + t * (16 * 32))); \
     } while (0)
 #define MFMAS(set)                                                                               \
     do {                                                                                         \
         _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
-            _Pragma("unroll") for (int t = 0; t < 8; ++t)                                        \
+            _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                      \
                 acc[f][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(wr[set][f]), xf[t], acc[f][t], 0, 0, 0); \
     } while (0)
     // stage st: k32 steps 2 st (weight set ws_) and 2 st + 1; X(st) is in LDS buffer st % 2
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int colw = n0 + wave * WAVE_COLS;
     if (colw >= NOUT) return;                               // wave past the ragged edge: its columns were recomputed only
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < NTT; ++t) {
         const int tr = t * 16 + li;
         if (tr < nrows) {
             uint16_t *orow = out + (size_t)(row0 + tr) * NOUT + colw + 4 * lg;
@@ -231,6 +232,40 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     }
 }
 
+template <int MODE, int NF, int NTT>
+static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
+                         const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
+                         uint16_t *out, hipStream_t st)
+{
+    constexpr int cols = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
+    const long n_nt = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
+    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, s->d,
+                       s->I, s->k, x, perm, offsets, counts, wa, wb, sched, out);
+}
+
+// Weight fragments per wave (NF) and 16-row token subtiles per tile (NTT).  An expert never receives more rows
+// than there are tokens, so T bounds the subtiles in use; narrow weight tiles keep every compute unit busy when
+// there are few token tiles.
+template <int MODE>
+static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16_t *x, const int32_t *perm,
+                           const int32_t *offsets, const int32_t *counts, const uint16_t *wa, const uint16_t *wb,
+                           const int32_t *sched, uint16_t *out, hipStream_t st)
+{
+#define GO(NF_, NTT_) launch_tiled<MODE, NF_, NTT_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, out, st)
+#define GO3(NTT_)                                          \
+    do {                                                   \
+        if constexpr (MODE == 1) {                         \
+            if (nf == 1) { GO(1, NTT_); break; }           \
+        }                                                  \
+        if (nf == 2) GO(2, NTT_); else GO(4, NTT_);        \
+    } while (0)
+    if (s->T <= 32) GO3(2);
+    else if (s->T <= 64) GO3(4);
+    else GO3(8);
+#undef GO3
+#undef GO
+}
+
 int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                        const int32_t *counts, const void *w1, const void *w3, const void *w2,
                        const uint8_t *expert_mask, void *y, void *workspace, int stages, hipStream_t st)
@@ -241,29 +276,22 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     uint16_t *act = (uint16_t *)((char *)workspace + L.act);
     int32_t *sched = (int32_t *)((char *)workspace + L.sched);
     const long max_mt = R / TM + (N < R ? N : R);
+    // token tiles to expect: every expert that can be non-empty has one, large experts have several
+    const long est_mt = (R + TM - 1) / TM > (N < R ? N : R) ? (R + TM - 1) / TM : (N < R ? N : R);
 
     if (stages & MOE_FFN_STAGE_UP) {
         hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
         MOE_CHECK_LAUNCH();
-        const long n_nt = (I + 255) / 256;
-        hipLaunchKernelGGL((ffn_tiled_kernel<0, 4>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
-                           (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1, (const uint16_t *)w3, sched, act);
+        dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
+                          (const uint16_t *)w3, sched, act, st);
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_DOWN) {
-        // 512-column tiles when that still gives every compute unit a block, else 256-column tiles
-        const long est_mt = (R + TM - 1) / TM;
-        if (est_mt * ((d + 511) / 512) >= 200) {
-            const long n_nt = (d + 511) / 512;
-            hipLaunchKernelGGL((ffn_tiled_kernel<1, 4>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
-                               (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr,
-                               sched, (uint16_t *)y);
-        } else {
-            const long n_nt = (d + 255) / 256;
-            hipLaunchKernelGGL((ffn_tiled_kernel<1, 2>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, d, I, k,
-                               (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2, (const uint16_t *)nullptr,
-                               sched, (uint16_t *)y);
-        }
+        // the widest weight tile that still leaves every compute unit a block (512
+        // columns, then 256 columns), else the narrowest (128 columns)
+        const int nf = est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
+        dispatch_tiled<1>(s, nf, max_mt, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
+                          (const uint16_t *)nullptr, sched, (uint16_t *)y, st);
         MOE_CHECK_LAUNCH();
     }
     return MOE_OK;

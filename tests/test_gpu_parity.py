@@ -148,6 +148,17 @@ def test_scaled_layers_tiled_path(gpu, name, T):
     _run_layer(B, Lm, cfg, T, [mask], B.FFN_TILED)
 
 
+@pytest.mark.parametrize("name,T", [("mixtral_s", 17), ("mixtral_s", 32), ("deepseek_s", 33), ("qwen15_s", 64),
+                                    ("qwen3_s", 48), ("mixtral_s", 65)])
+def test_scaled_layers_mid_sized_batches(gpu, name, T):
+    # batches between the decode kernels' limit and one full token tile: the tiled kernels run with 2, 4 or 8
+    # token subtiles (an expert cannot receive more rows than there are tokens) and narrow down-projection tiles
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"mid {name} T={T}", flush=True)
+    _run_layer(B, Lm, cfg, T, [wl.mask_random(cfg, (3 * cfg.N) // 4), None], B.FFN_AUTO)
+
+
 @pytest.mark.parametrize("name,T", [("mixtral_s", 1), ("mixtral_s", 16), ("deepseek_s", 16), ("qwen15_s", 1),
                                     ("qwen3_s", 16), ("qwen3_s", 5)])
 def test_scaled_layers_skinny_path(gpu, name, T):
