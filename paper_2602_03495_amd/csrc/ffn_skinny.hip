@@ -226,6 +226,9 @@ static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, 
         hipLaunchKernelGGL((skinny_down_kernel<MAXS, 1, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, spb, act, offsets, counts, w2, mask, y, partial);
 }
 
+int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
+                       const void *, const void *, const uint8_t *, void *, void *, int, hipStream_t);
+
 int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                         const int32_t *counts, const void *w1, const void *w3, const void *w2,
                         const uint8_t *expert_mask, void *y, void *workspace, int stages, hipStream_t st)
@@ -251,6 +254,10 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         MOE_CHECK_LAUNCH();
     }
     // ---- down projection ---------------------------------------------------------------------------
+    // With a short inner size a wave's share of K is a handful of steps and the cross-wave reduction dominates:
+    // the tiled kernel, where every wave owns whole weight rows, is the faster one there.
+    if ((stages & MOE_FFN_STAGE_DOWN) && I <= MOE_SKINNY_DOWN_MIN_I)
+        return moe_ffn_tiled_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, MOE_FFN_STAGE_DOWN, st);
     if (stages & MOE_FFN_STAGE_DOWN) {
         const int total = I >> 5;
         const int nsplit = moe_skinny_nsplit(I);

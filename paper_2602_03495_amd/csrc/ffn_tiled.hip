@@ -62,12 +62,13 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
 // Weight tile of a block: 8 waves x NF fragments x 16 rows.
-template <int MODE, int NF, int NTT = 8>
+template <int MODE, int NF, int NTT, bool DIRECT>
 __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
     const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
-    const int32_t *__restrict__ sched, uint16_t *__restrict__ out)      // MODE 0: act [R,I]; MODE 1: y [R,d]
+    const int32_t *__restrict__ sched, const uint8_t *__restrict__ mask,   // DIRECT: mask instead of a schedule
+    uint16_t *__restrict__ out)                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
 
@@ -79,20 +80,30 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int n_nt = (NOUT + NT_COLS - 1) / NT_COLS;
 
     // ---- which item -------------------------------------------------------------------------------
-    const int n_mt = sched[0];
-    const int total = n_mt * n_nt;
-    const int pid = blockIdx.x;
-    if (pid >= total) return;
-    int L;
-    {
-        const int q = total / NUM_XCD, rem = total % NUM_XCD;
-        const int xcd = pid % NUM_XCD, loc = pid / NUM_XCD;
-        L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
+    int e, mt, nt;
+    if (DIRECT) {
+        // at most one token tile per expert (T <= 128): the grid is (weight tiles, experts), no schedule needed
+        e = blockIdx.y;
+        nt = blockIdx.x;
+        mt = 0;
+        if (counts[e] <= 0 || (mask != nullptr && mask[e] == 0)) return;
+    } else {
+        const int n_mt = sched[0];
+        const int total = n_mt * n_nt;
+        const int pid = blockIdx.x;
+        if (pid >= total) return;
+        int L;
+        {
+            const int q = total / NUM_XCD, rem = total % NUM_XCD;
+            const int xcd = pid % NUM_XCD, loc = pid / NUM_XCD;
+            L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
+        }
+        const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
+        e = ent.x;
+        const int local = L - ent.y * n_nt;
+        mt = local % ent.z;
+        nt = local / ent.z;
     }
-    const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
-    const int e = ent.x;
-    const int local = L - ent.y * n_nt;
-    const int mt = local % ent.z, nt = local / ent.z;
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;
     nrows = nrows > TM ? TM : nrows;
@@ -232,36 +243,39 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     }
 }
 
-template <int MODE, int NF, int NTT>
+template <int MODE, int NF, int NTT, bool DIRECT>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
-                         uint16_t *out, hipStream_t st)
+                         const uint8_t *mask, uint16_t *out, hipStream_t st)
 {
     constexpr int cols = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
     const long n_nt = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
-    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT>), dim3((unsigned)(max_mt * n_nt)), dim3(TILED_THREADS), 0, st, s->d,
-                       s->I, s->k, x, perm, offsets, counts, wa, wb, sched, out);
+    const dim3 grid = DIRECT ? dim3((unsigned)n_nt, (unsigned)s->N) : dim3((unsigned)(max_mt * n_nt));
+    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, x, perm,
+                       offsets, counts, wa, wb, sched, mask, out);
 }
 
 // Weight fragments per wave (NF) and 16-row token subtiles per tile (NTT).  An expert never receives more rows
-// than there are tokens, so T bounds the subtiles in use; narrow weight tiles keep every compute unit busy when
-// there are few token tiles.
+// than there are tokens, so T bounds the subtiles in use, and up to 128 tokens every expert has at most one token
+// tile, which needs no schedule; narrow weight tiles keep every compute unit busy when there are few token tiles.
 template <int MODE>
 static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16_t *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *counts, const uint16_t *wa, const uint16_t *wb,
-                           const int32_t *sched, uint16_t *out, hipStream_t st)
+                           const int32_t *sched, const uint8_t *mask, uint16_t *out, hipStream_t st)
 {
-#define GO(NF_, NTT_) launch_tiled<MODE, NF_, NTT_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, out, st)
-#define GO3(NTT_)                                          \
+#define GO(NF_, NTT_, D_) launch_tiled<MODE, NF_, NTT_, D_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, st)
+#define GO3(NTT_, D_)                                      \
     do {                                                   \
         if constexpr (MODE == 1) {                         \
-            if (nf == 1) { GO(1, NTT_); break; }           \
+            if (nf == 1) { GO(1, NTT_, D_); break; }       \
         }                                                  \
-        if (nf == 2) GO(2, NTT_); else GO(4, NTT_);        \
+        if (nf == 2) GO(2, NTT_, D_); else GO(4, NTT_, D_);\
     } while (0)
-    if (s->T <= 32) GO3(2);
-    else if (s->T <= 64) GO3(4);
-    else GO3(8);
+    if (s->T <= 16) GO3(1, true);
+    else if (s->T <= 32) GO3(2, true);
+    else if (s->T <= 64) GO3(4, true);
+    else if (s->T <= TM) GO3(8, true);
+    else GO3(8, false);
 #undef GO3
 #undef GO
 }
@@ -280,18 +294,21 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     const long est_mt = (R + TM - 1) / TM > (N < R ? N : R) ? (R + TM - 1) / TM : (N < R ? N : R);
 
     if (stages & MOE_FFN_STAGE_UP) {
-        hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
-        MOE_CHECK_LAUNCH();
+        if (s->T > TM) {
+            hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
+            MOE_CHECK_LAUNCH();
+        }
         dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
-                          (const uint16_t *)w3, sched, act, st);
+                          (const uint16_t *)w3, sched, expert_mask, act, st);
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_DOWN) {
         // the widest weight tile that still leaves every compute unit a block (512
         // columns, then 256 columns), else the narrowest (128 columns)
-        const int nf = est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
+        const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
+                       : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
         dispatch_tiled<1>(s, nf, max_mt, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
-                          (const uint16_t *)nullptr, sched, (uint16_t *)y, st);
+                          (const uint16_t *)nullptr, sched, expert_mask, (uint16_t *)y, st);
         MOE_CHECK_LAUNCH();
     }
     return MOE_OK;

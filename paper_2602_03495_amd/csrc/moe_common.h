@@ -105,6 +105,7 @@ struct moe_ws_layout {
 #define MOE_SKINNY_WAVES 4          // waves per block on the skinny path
 #define MOE_SKINNY_MAX_STEPS 32     // 32-wide K steps a wave may hold in registers (K <= 1024 per wave)
 #define MOE_TILE_M 128              // token rows per tile on the tiled path
+#define MOE_SKINNY_DOWN_MIN_I 2048  // decode-sized down projections with I up to this run on the tiled kernel
 
 static inline int moe_skinny_nsplit(int K)
 {

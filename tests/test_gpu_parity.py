@@ -176,6 +176,15 @@ def test_skinny_split_k_down_projection(gpu):
     _run_layer(B, Lm, cfg, 16, [wl.mask_random(cfg, 6)], B.FFN_SKINNY)
 
 
+def test_skinny_down_projection_without_split(gpu):
+    # inner sizes in (2048, 4096] keep the decode-sized down projection on the skinny kernel, one block per row
+    # tile over all of K; up to 2048 it runs on the tiled kernel (covered by the scaled shapes above)
+    B, Lm = gpu
+    cfg = wl.scaled(wl.CONFIGS["mixtral"], d=256, I=2304)
+    _run_layer(B, Lm, cfg, 16, [wl.mask_random(cfg, 6), None], B.FFN_SKINNY)
+    _run_layer(B, Lm, cfg, 3, [None], B.FFN_SKINNY)
+
+
 def test_tiled_and_skinny_paths_agree_and_runs_are_deterministic(gpu):
     B, Lm = gpu
     cfg = SMALL["qwen3_s"]
