@@ -20,8 +20,13 @@
 //     of one token: SwiGLU is applied in registers and the result leaves as one 8-byte store.
 // A work item is (expert, 128-row token tile, weight tile); the item list is built on the device from
 // counts/offsets/mask (tile_schedule_kernel), so empty and masked-off experts cost nothing and there is no host
-// round trip.  Block ids are remapped so that every XCD (own L2) works on a contiguous run of items ordered
-// expert-major, weight tile, token tile: the token tiles that share a weight tile run side by side on one XCD.
+// round trip.  Up to 128 tokens an expert has at most one token tile and every wave derives the list of working
+// experts itself from two ballots, so no schedule kernel runs.  Block ids are remapped so that every XCD (own
+// L2) works on a contiguous run of items ordered expert-major, weight tile, token tile: the token tiles that
+// share a weight tile run side by side on one XCD (measured: the same items spread round-robin over the XCDs
+// run up to 40 % slower, even with one token tile per expert).
+// Tiles are rarely full away from large prefill batches: the launch bounds the 16-row subtiles by T, and when
+// the average expert has fewer than 128 rows each block runs the body sized for its own row count.
 // Each item walks K as a ring starting at a tile-dependent offset, which spreads concurrently running tiles
 // over the address space; the summation order is a function of (expert, weight tile) only, so results are
 // reproducible.
@@ -61,52 +66,19 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
 
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
-// Weight tile of a block: 8 waves x NF fragments x 16 rows.
-template <int MODE, int NF, int NTT, bool DIRECT>
-__global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
-    int d, int I, int k, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
-    const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
-    const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
-    const int32_t *__restrict__ sched, const uint8_t *__restrict__ mask,   // DIRECT: mask instead of a schedule
-    uint16_t *__restrict__ out)                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
+// Weight tile of a block: 8 waves x NF fragments x 16 rows.  NTT = 16-row token subtiles computed (rows past
+// nrows are clamped copies whose results are dropped).
+template <int MODE, int NF, int NTT>
+__device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int I, int k, const uint16_t *__restrict__ xsrc,
+                                          const int32_t *__restrict__ perm, const uint16_t *__restrict__ wa,
+                                          const uint16_t *__restrict__ wb, uint16_t *__restrict__ out, int e, int nt,
+                                          int row0, int nrows)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
-
     constexpr int HF = MODE == 0 ? NF / 2 : NF;           // fragments per matrix per wave
     constexpr int WAVE_COLS = HF * 16;                     // output columns a wave produces
     constexpr int NT_COLS = 8 * WAVE_COLS;                 // output columns per block
     const int K = MODE == 0 ? d : I;
     const int NOUT = MODE == 0 ? I : d;
-    const int n_nt = (NOUT + NT_COLS - 1) / NT_COLS;
-
-    // ---- which item -------------------------------------------------------------------------------
-    int e, mt, nt;
-    if (DIRECT) {
-        // at most one token tile per expert (T <= 128): the grid is (weight tiles, experts), no schedule needed
-        e = blockIdx.y;
-        nt = blockIdx.x;
-        mt = 0;
-        if (counts[e] <= 0 || (mask != nullptr && mask[e] == 0)) return;
-    } else {
-        const int n_mt = sched[0];
-        const int total = n_mt * n_nt;
-        const int pid = blockIdx.x;
-        if (pid >= total) return;
-        int L;
-        {
-            const int q = total / NUM_XCD, rem = total % NUM_XCD;
-            const int xcd = pid % NUM_XCD, loc = pid / NUM_XCD;
-            L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
-        }
-        const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
-        e = ent.x;
-        const int local = L - ent.y * n_nt;
-        mt = local % ent.z;
-        nt = local / ent.z;
-    }
-    const int row0 = offsets[e] + mt * TM;
-    int nrows = counts[e] - mt * TM;
-    nrows = nrows > TM ? TM : nrows;
     const int n0 = nt * NT_COLS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -243,6 +215,82 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     }
 }
 
+// NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
+// body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
+template <int MODE, int NF, int NTT_MAX, bool DIRECT, bool DYN>
+__global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
+    int d, int I, int k, int N, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
+    const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
+    const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
+    const int32_t *__restrict__ sched, const uint8_t *__restrict__ mask,   // DIRECT: mask instead of a schedule
+    uint16_t *__restrict__ out)                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
+{
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
+    constexpr int NT_COLS = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
+    const int n_nt = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;
+
+    // ---- which item -------------------------------------------------------------------------------
+    int e, mt, nt, total;
+    int first_tile = 0, tiles_e = 1;
+    unsigned long long act_lo = 0, act_hi = 0;
+    if (DIRECT) {
+        // at most one token tile per expert (T <= 128): every wave derives the list of working experts itself,
+        // as two 64-bit masks, so no schedule has to be built first
+        const int l = threadIdx.x & 63;
+        const bool on_lo = l < N && counts[l] > 0 && (mask == nullptr || mask[l] != 0);
+        const bool on_hi = l + 64 < N && counts[l + 64] > 0 && (mask == nullptr || mask[l + 64] != 0);
+        act_lo = __ballot(on_lo);
+        act_hi = __ballot(on_hi);
+        total = (__popcll(act_lo) + __popcll(act_hi)) * n_nt;
+    } else {
+        total = sched[0] * n_nt;
+    }
+    const int pid = blockIdx.x;
+    if (pid >= total) return;
+    int L;
+    {
+        const int q = total / NUM_XCD, rem = total % NUM_XCD;
+        const int xcd = pid % NUM_XCD, loc = pid / NUM_XCD;
+        L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
+    }
+    if (DIRECT) {
+        // the (L / n_nt)-th working expert: the lane whose own bit is set and has that many set bits below it
+        int a = L / n_nt;
+        const int n_lo = __popcll(act_lo);
+        unsigned long long m = act_lo;
+        int base = 0;
+        if (a >= n_lo) {
+            a -= n_lo;
+            m = act_hi;
+            base = 64;
+        }
+        const int l = threadIdx.x & 63;
+        const unsigned long long below = l == 0 ? 0ull : (m << (64 - l));     // bits of m under position l, shifted up
+        const bool mine = ((m >> l) & 1ull) != 0 && __popcll(below) == a;
+        e = base + __ffsll((unsigned long long)__ballot(mine)) - 1;
+        mt = 0;
+        nt = L % n_nt;
+    } else {
+        const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
+        e = ent.x;
+        first_tile = ent.y;
+        tiles_e = ent.z;
+        const int local = L - first_tile * n_nt;
+        mt = local % tiles_e;
+        nt = local / tiles_e;
+    }
+    const int row0 = offsets[e] + mt * TM;
+    int nrows = counts[e] - mt * TM;
+    nrows = nrows > TM ? TM : nrows;
+#define BODY(n) tile_body<MODE, NF, n>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows)
+    if (!DYN) BODY(NTT_MAX);
+    else if (NTT_MAX == 1 || nrows <= 16) BODY(1);
+    else if (NTT_MAX == 2 || nrows <= 32) BODY(2);
+    else if (NTT_MAX == 4 || nrows <= 64) BODY(4);
+    else BODY(8);
+#undef BODY
+}
+
 template <int MODE, int NF, int NTT, bool DIRECT>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
@@ -250,9 +298,16 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
 {
     constexpr int cols = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
     const long n_nt = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
-    const dim3 grid = DIRECT ? dim3((unsigned)n_nt, (unsigned)s->N) : dim3((unsigned)(max_mt * n_nt));
-    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, x, perm,
-                       offsets, counts, wa, wb, sched, mask, out);
+    const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
+    const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
+    // a block sizes its body to its own rows when tiles are sparsely filled on average (under 128 rows per expert);
+    // with fuller tiles the single full-size body is the faster code
+    if ((long)s->T * s->k >= (long)TM * s->N)
+        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, false>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, s->N, x, perm,
+                           offsets, counts, wa, wb, sched, mask, out);
+    else
+        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, true>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, s->N, x, perm,
+                           offsets, counts, wa, wb, sched, mask, out);
 }
 
 // Weight fragments per wave (NF) and 16-row token subtiles per tile (NTT).  An expert never receives more rows
