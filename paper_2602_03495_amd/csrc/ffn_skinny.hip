@@ -8,7 +8,9 @@
 // inner loop is "global_load, mfma" and nothing else.  K is split over the 4 waves of a block (and, for the
 // long down projection, over several blocks); partial 16x16 tiles are reduced through LDS (and through an
 // fp32 scratch + a finishing kernel when K is split over blocks), in a fixed order, so results are
-// reproducible.  Untouched and masked-off experts cost one early-exit block each and no memory traffic.
+// reproducible.  The grid covers the experts that can be non-empty; blocks find their (working expert, row block)
+// item themselves and run the compacted item list in XCD-contiguous order, so untouched and masked-off experts
+// cost no memory traffic and the blocks of one expert share an L2.
 #include "moe_common.h"
 
 #define SK_WAVES MOE_SKINNY_WAVES
@@ -25,16 +27,16 @@ __device__ __forceinline__ void load_x_frags(u32x4 (&xf)[MAXS], const uint16_t *
     }
 }
 
-// act[p, i] = silu(W1_e[i,:] . x_p) * (W3_e[i,:] . x_p)   for the rows p of expert e = blockIdx.y
+// act[p, i] = silu(W1_e[i,:] . x_p) * (W3_e[i,:] . x_p)   for the rows p of the block's expert
 template <int MAXS, int RT>
 __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
-    int d, int k, int I, const uint16_t *__restrict__ h, const int32_t *__restrict__ perm,
+    int d, int k, int I, int N, int blocks_per_expert, const uint16_t *__restrict__ h, const int32_t *__restrict__ perm,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts, const uint16_t *__restrict__ w1,
     const uint16_t *__restrict__ w3, const uint8_t *__restrict__ mask, uint16_t *__restrict__ act)
 {
-    const int e = blockIdx.y;
+    int e, bx;
+    if (!moe_working_item(N, counts, mask, blocks_per_expert, blockIdx.x, e, bx)) return;
     const int c = counts[e];
-    if (c <= 0 || (mask != nullptr && mask[e] == 0)) return;
     __shared__ float red[SK_WAVES][RT][2][256];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
         const int tok = valid ? perm[off + i] / k : 0;
         load_x_frags<MAXS>(xf, h + (size_t)tok * d, valid, s0, ns, g);
     }
-    const int i0 = blockIdx.x * (16 * RT);
+    const int i0 = bx * (16 * RT);
     const int last = ns > 0 ? ns - 1 : 0;   // steps past the wave's range re-read its last step against a zero fragment
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -103,20 +105,21 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
 // y[p, f] (or a split-K partial of it) = W2_e[f,:] . act[p,:]
 template <int MAXS, int RT, bool DIRECT>
 __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
-    int d, int I, int R, int steps_per_block, const uint16_t *__restrict__ act, const int32_t *__restrict__ offsets,
-    const int32_t *__restrict__ counts, const uint16_t *__restrict__ w2, const uint8_t *__restrict__ mask,
-    uint16_t *__restrict__ y, float *__restrict__ partial)
+    int d, int I, int R, int N, int row_blocks, int nsplit, int steps_per_block, const uint16_t *__restrict__ act,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts, const uint16_t *__restrict__ w2,
+    const uint8_t *__restrict__ mask, uint16_t *__restrict__ y, float *__restrict__ partial)
 {
-    const int e = blockIdx.z;
+    int e, local;
+    if (!moe_working_item(N, counts, mask, row_blocks * nsplit, blockIdx.x, e, local)) return;
+    const int bx = local % row_blocks, by = local / row_blocks;    // row block, K split
     const int c = counts[e];
-    if (c <= 0 || (mask != nullptr && mask[e] == 0)) return;
     __shared__ float red[SK_WAVES][RT][256];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int off = offsets[e];
     const int total = I >> 5;
-    const int b0 = blockIdx.y * steps_per_block;
+    const int b0 = by * steps_per_block;
     int bn = total - b0;
     bn = bn > steps_per_block ? steps_per_block : bn;
     const int per = (steps_per_block + SK_WAVES - 1) / SK_WAVES;
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
         const bool valid = i < c;
         load_x_frags<MAXS>(xf, act + (size_t)(off + (valid ? i : 0)) * I, valid, s0, ns, g);
     }
-    const int f0 = blockIdx.x * (16 * RT);
+    const int f0 = bx * (16 * RT);
     const int last = ns > 0 ? ns - 1 : 0;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -163,7 +166,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
             if (DIRECT)
                 y[(size_t)(off + j) * d + f] = (uint16_t)f32_to_bf16(sum);
             else
-                partial[((size_t)blockIdx.y * R + off + j) * d + f] = sum;
+                partial[((size_t)by * R + off + j) * d + f] = sum;
         }
     }
 }
@@ -201,29 +204,29 @@ static int pick_rt(int tiles_per_expert, int est_active)
 }
 
 template <int MAXS>
-static void launch_up(int rt, dim3 grid, hipStream_t st, int d, int k, int I, const uint16_t *h, const int32_t *perm,
-                      const int32_t *offsets, const int32_t *counts, const uint16_t *w1, const uint16_t *w3,
-                      const uint8_t *mask, uint16_t *act)
+static void launch_up(int rt, dim3 grid, hipStream_t st, int d, int k, int I, int N, int bpe, const uint16_t *h,
+                      const int32_t *perm, const int32_t *offsets, const int32_t *counts, const uint16_t *w1,
+                      const uint16_t *w3, const uint8_t *mask, uint16_t *act)
 {
     if (rt == 4)
-        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 4>), grid, dim3(SK_THREADS), 0, st, d, k, I, h, perm, offsets, counts, w1, w3, mask, act);
+        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 4>), grid, dim3(SK_THREADS), 0, st, d, k, I, N, bpe, h, perm, offsets, counts, w1, w3, mask, act);
     else if (rt == 2)
-        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 2>), grid, dim3(SK_THREADS), 0, st, d, k, I, h, perm, offsets, counts, w1, w3, mask, act);
+        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 2>), grid, dim3(SK_THREADS), 0, st, d, k, I, N, bpe, h, perm, offsets, counts, w1, w3, mask, act);
     else
-        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 1>), grid, dim3(SK_THREADS), 0, st, d, k, I, h, perm, offsets, counts, w1, w3, mask, act);
+        hipLaunchKernelGGL((skinny_up_kernel<MAXS, 1>), grid, dim3(SK_THREADS), 0, st, d, k, I, N, bpe, h, perm, offsets, counts, w1, w3, mask, act);
 }
 
 template <int MAXS, bool DIRECT>
-static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, int spb, const uint16_t *act,
-                        const int32_t *offsets, const int32_t *counts, const uint16_t *w2, const uint8_t *mask,
-                        uint16_t *y, float *partial)
+static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, int N, int rb, int nsplit, int spb,
+                        const uint16_t *act, const int32_t *offsets, const int32_t *counts, const uint16_t *w2,
+                        const uint8_t *mask, uint16_t *y, float *partial)
 {
     if (rt == 4)
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 4, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 4, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
     else if (rt == 2)
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 2, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 2, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
     else
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 1, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 1, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
 }
 
 int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
@@ -246,9 +249,10 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         const int per = ((d >> 5) + SK_WAVES - 1) / SK_WAVES;
         const int tiles = (I + 15) / 16;
         const int rt = pick_rt(tiles, est_active);
-        dim3 grid((tiles + rt - 1) / rt, N);
+        const int bpe = (tiles + rt - 1) / rt;               // blocks per working expert
+        dim3 grid((unsigned)(bpe * est_active));
         const uint16_t *hp = (const uint16_t *)h, *p1 = (const uint16_t *)w1, *p3 = (const uint16_t *)w3;
-#define UP(n) case n: launch_up<4 * n>(rt, grid, st, d, k, I, hp, perm, offsets, counts, p1, p3, expert_mask, act); break;
+#define UP(n) case n: launch_up<4 * n>(rt, grid, st, d, k, I, N, bpe, hp, perm, offsets, counts, p1, p3, expert_mask, act); break;
         switch ((per + 3) / 4) { UP(1) UP(2) UP(3) UP(4) UP(5) UP(6) UP(7) UP(8) default: return MOE_EUNSUPPORTED; }
 #undef UP
         MOE_CHECK_LAUNCH();
@@ -265,10 +269,11 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         const int per = (spb + SK_WAVES - 1) / SK_WAVES;
         const int tiles = (d + 15) / 16;
         const int rt = pick_rt(tiles * nsplit, est_active);
-        dim3 grid((tiles + rt - 1) / rt, nsplit, N);
+        const int rbk = (tiles + rt - 1) / rt;               // row blocks per working expert
+        dim3 grid((unsigned)(rbk * nsplit * est_active));
         const uint16_t *p2 = (const uint16_t *)w2;
         uint16_t *yp = (uint16_t *)y;
-#define DN(n, direct) case n: launch_down<4 * n, direct>(rt, grid, st, d, I, R, spb, act, offsets, counts, p2, expert_mask, yp, partial); break;
+#define DN(n, direct) case n: launch_down<4 * n, direct>(rt, grid, st, d, I, R, N, rbk, nsplit, spb, act, offsets, counts, p2, expert_mask, yp, partial); break;
         if (nsplit == 1) {
             switch ((per + 3) / 4) { DN(1, true) DN(2, true) DN(3, true) DN(4, true) DN(5, true) DN(6, true) DN(7, true) DN(8, true) default: return MOE_EUNSUPPORTED; }
             MOE_CHECK_LAUNCH();

@@ -33,7 +33,7 @@
 #include "moe_common.h"
 
 #define TM MOE_TILE_M     // token rows per tile
-#define NUM_XCD 8
+#define NUM_XCD MOE_NUM_XCD
 #define TILED_THREADS 512
 
 // sched layout: int32 hdr[4] = {n_token_tiles, 0, 0, 0}; then int4 per token tile {expert, first_tile, n_tiles_of_expert, 0}
@@ -230,54 +230,23 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int n_nt = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;
 
     // ---- which item -------------------------------------------------------------------------------
-    int e, mt, nt, total;
-    int first_tile = 0, tiles_e = 1;
-    unsigned long long act_lo = 0, act_hi = 0;
+    int e, mt, nt;
     if (DIRECT) {
-        // at most one token tile per expert (T <= 128): every wave derives the list of working experts itself,
-        // as two 64-bit masks, so no schedule has to be built first
-        const int l = threadIdx.x & 63;
-        const bool on_lo = l < N && counts[l] > 0 && (mask == nullptr || mask[l] != 0);
-        const bool on_hi = l + 64 < N && counts[l + 64] > 0 && (mask == nullptr || mask[l + 64] != 0);
-        act_lo = __ballot(on_lo);
-        act_hi = __ballot(on_hi);
-        total = (__popcll(act_lo) + __popcll(act_hi)) * n_nt;
+        // at most one token tile per expert (T <= 128): no schedule has been built
+        if (!moe_working_item(N, counts, mask, n_nt, blockIdx.x, e, nt)) return;
+        mt = 0;
     } else {
-        total = sched[0] * n_nt;
-    }
-    const int pid = blockIdx.x;
-    if (pid >= total) return;
-    int L;
-    {
+        const int total = sched[0] * n_nt;
+        const int pid = blockIdx.x;
+        if (pid >= total) return;
         const int q = total / NUM_XCD, rem = total % NUM_XCD;
         const int xcd = pid % NUM_XCD, loc = pid / NUM_XCD;
-        L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
-    }
-    if (DIRECT) {
-        // the (L / n_nt)-th working expert: the lane whose own bit is set and has that many set bits below it
-        int a = L / n_nt;
-        const int n_lo = __popcll(act_lo);
-        unsigned long long m = act_lo;
-        int base = 0;
-        if (a >= n_lo) {
-            a -= n_lo;
-            m = act_hi;
-            base = 64;
-        }
-        const int l = threadIdx.x & 63;
-        const unsigned long long below = l == 0 ? 0ull : (m << (64 - l));     // bits of m under position l, shifted up
-        const bool mine = ((m >> l) & 1ull) != 0 && __popcll(below) == a;
-        e = base + __ffsll((unsigned long long)__ballot(mine)) - 1;
-        mt = 0;
-        nt = L % n_nt;
-    } else {
+        const int L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
         const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
         e = ent.x;
-        first_tile = ent.y;
-        tiles_e = ent.z;
-        const int local = L - first_tile * n_nt;
-        mt = local % tiles_e;
-        nt = local / tiles_e;
+        const int local = L - ent.y * n_nt;
+        mt = local % ent.z;
+        nt = local / ent.z;
     }
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;

@@ -84,6 +84,40 @@ __device__ __forceinline__ float wave_sum_dpp(float v)
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
+// ---- work items of the experts that have rows and are masked on, without a schedule pass --------------------
+// A launch of (upper bound of working experts) x per_expert blocks: every wave derives the working set itself
+// as two 64-bit ballots over counts/mask, the block id is remapped so that each of the 8 XCDs (own L2) gets one
+// contiguous run of the compacted item list (expert-major), and the item's expert is found by rank among the set
+// bits.  Returns false for a block beyond the list.  All 64 lanes of the wave must call it.
+#define MOE_NUM_XCD 8
+__device__ __forceinline__ bool moe_working_item(int N, const int32_t *__restrict__ counts, const uint8_t *__restrict__ mask,
+                                                 int per_expert, int pid, int &e, int &local)
+{
+    const int l = threadIdx.x & 63;
+    const bool on_lo = l < N && counts[l] > 0 && (mask == nullptr || mask[l] != 0);
+    const bool on_hi = l + 64 < N && counts[l + 64] > 0 && (mask == nullptr || mask[l + 64] != 0);
+    const unsigned long long act_lo = __ballot(on_lo), act_hi = __ballot(on_hi);
+    const int n_lo = __popcll(act_lo);
+    const int total = (n_lo + __popcll(act_hi)) * per_expert;
+    if (pid >= total) return false;
+    const int q = total / MOE_NUM_XCD, rem = total % MOE_NUM_XCD;
+    const int xcd = pid % MOE_NUM_XCD, loc = pid / MOE_NUM_XCD;
+    const int L = xcd < rem ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
+    int a = L / per_expert;
+    local = L - a * per_expert;
+    unsigned long long m = act_lo;
+    int base = 0;
+    if (a >= n_lo) {
+        a -= n_lo;
+        m = act_hi;
+        base = 64;
+    }
+    const unsigned long long below = l == 0 ? 0ull : (m << (64 - l));     // the bits of m under position l
+    const bool mine = ((m >> l) & 1ull) != 0 && __popcll(below) == a;
+    e = base + __ffsll((unsigned long long)__ballot(mine)) - 1;
+    return true;
+}
+
 #define MOE_CHECK_LAUNCH()                       \
     do {                                         \
         if (hipGetLastError() != hipSuccess)     \
