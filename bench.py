@@ -139,6 +139,12 @@ def main():
         st.calibrate(bias)
         res = st.run(args.stack_steps, bias, use_res_vec=True)
         raw = st.run(min(args.stack_steps, 64), bias, use_res_vec=False)
+        # cost of the prediction per layer: issued inline, on a second stream next to routing/FFN/combine, or not at all
+        n_ov = min(args.stack_steps, 64)
+        ov = {mode: st.run(n_ov, bias, predict=mode).seconds / n_ov / args.stack_layers * 1e6 for mode in ("off", "inline", "side", "fused")}
+        log(f"[bench] stack us/layer, eager launches: no prediction {ov['off']:.1f}, inline {ov['inline']:.1f}, side stream {ov['side']:.1f}, fused with routing {ov['fused']:.1f}")
+        ovg = {mode: st.layer_graph_seconds(bias, predict=mode) * 1e6 for mode in ("off", "inline", "side", "fused")}
+        log(f"[bench] one layer as a replayed graph, us: no prediction {ovg['off']:.1f}, inline {ovg['inline']:.1f}, side stream {ovg['side']:.1f}, fused with routing {ovg['fused']:.1f}")
         c = res.counts
         # Workload-Aware Cache Replacement (Alg. 2) replayed over the measured histogram stream, one cache per layer:
         # 64 of 128 experts resident, w_size = 4, u_size = 8; hit rate = share of the routed rows that found their
@@ -164,6 +170,8 @@ def main():
                "us_per_layer": res.seconds / args.stack_steps / args.stack_layers * 1e6, "dtype": "bf16", "data": "synthetic",
                "config": {"workload": "qwen3-30b-a3b-shaped decode stack, AR(1) gate bias rho=0.9, mask = top half by previous step"},
                "prediction_accuracy_with_res_vec": res.acc, "prediction_accuracy_without_res_vec": raw.acc,
+               "prediction_overlap_us_per_layer": {"eager": {"no_prediction": ov["off"], "inline": ov["inline"], "side_stream": ov["side"], "fused_with_routing": ov["fused"]},
+                                                   "graph_replay": {"no_prediction": ovg["off"], "inline": ovg["inline"], "side_stream": ovg["side"], "fused_with_routing": ovg["fused"]}},
                "cache_replacement": {"policy": "workload-aware (Alg. 2), 64 of 128 resident, w_size 4, u_size 8",
                                      "hit_rate": hits / tot, "hit_rate_static_cache": hits_static / tot,
                                      "host_us_per_layer_step": t_sched / (args.stack_layers * args.stack_steps) * 1e6},

@@ -101,12 +101,24 @@ int moe_route(const moe_shape *s, const void *h, const void *gate_w, const float
  *
  * The logits are evaluated as h.W + (res_vec.W + bias), which equals (h + res_vec).W + bias up to
  * fp32 rounding; h + res_vec is never rounded to bf16.
- * h [T,d] bf16, res_vec [d] fp32, next_gate_w [N,d] bf16, next_gate_bias [N] fp32 or NULL,
+ * h [T,d] bf16, res_vec [d] fp32 (16-byte aligned), next_gate_w [N,d] bf16, next_gate_bias [N] fp32 or NULL,
  * pred_counts [N] int32 out, top_experts [p] int32 out (1 <= p <= N): all [device].
  */
 int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec, const void *next_gate_w,
                          const float *next_gate_bias, int p, int32_t *pred_counts, int32_t *top_experts,
                          void *workspace, void *stream);
+
+/*
+ * moe_route of this layer and moe_predict_workload for the next one in a single call, with the results of the two
+ * calls made one after the other (same arguments, same outputs, bit for bit).  The features h are the input of
+ * both gates (Section "Residual-Based Prefetching": the prediction uses the current layer's features), so at decode
+ * sizes (T <= 16 and T*k <= 128) the two gates are evaluated side by side by the same pair of launches; larger
+ * batches run the two calls in sequence.  workspace is required (not NULL).
+ */
+int moe_route_predict(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                      int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                      int32_t *inv_perm, const float *res_vec, const void *next_gate_w, const float *next_gate_bias,
+                      int p, int32_t *pred_counts, int32_t *top_experts, void *workspace, void *stream);
 
 /*
  * Expert weights are consumed in a packed, MFMA-fragment-ordered layout (the expert weights are static, so this
@@ -182,6 +194,25 @@ int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32
  * h [T,d] bf16, w_sg [d] bf16, scale [T] fp32 out: all [device].  Uses s->T and s->d only.
  */
 int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *scale, void *stream);
+
+/*
+ * Calibration of res_vec (Section "Residual-Based Prefetching", the res_vec equation): the mean, over the tokens
+ * of a calibration set, of the difference between a token's input feature at the next MoE layer and at this one.
+ *
+ *   moe_res_vec_accumulate:  acc_sum[j] += sum over r < n of ( h_next[r,j] - h_cur[r,j] )      (float64)
+ *   moe_res_vec_finish:      res_vec[j]  = (float)( acc_sum[j] / n_total )
+ *
+ * The calibration set may arrive in any number of batches: zero acc_sum once, accumulate every batch, finish with
+ * the total number of tokens.  Sums are formed in a fixed order (no atomics), in float64.
+ * h_cur, h_next [n,d] bf16 [device], 16-byte aligned, the same n tokens row by row; acc_sum [d] float64 [device],
+ * in/out; workspace [device], 8-byte aligned, >= moe_res_vec_workspace_bytes(d) bytes; res_vec [d] fp32 [device]
+ * out.  d a multiple of 8, 8 <= d <= 8192; n >= 0 (n = 0 changes nothing); n_total >= 1.
+ * Errors: MOE_EINVAL for a NULL or misaligned pointer or a size out of range.
+ */
+size_t moe_res_vec_workspace_bytes(int d);
+int moe_res_vec_accumulate(int n, int d, const void *h_cur, const void *h_next, double *acc_sum, void *workspace,
+                           void *stream);
+int moe_res_vec_finish(int d, const double *acc_sum, int64_t n_total, float *res_vec, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------------
  * Host-side scheduling policies fed by the workload histograms (all pointers [host]; nothing touches the GPU).

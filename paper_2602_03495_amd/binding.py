@@ -17,7 +17,8 @@ NORM_NONE, NORM_RENORM = 0, 1
 
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
            "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
-           "moe_expert_times", "moe_greedy_assign", "moe_cache_step"]
+           "moe_expert_times", "moe_greedy_assign", "moe_cache_step", "moe_res_vec_workspace_bytes",
+           "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict"]
 
 
 class MoeShape(C.Structure):
@@ -43,6 +44,7 @@ def load_library():
         _lib.moe_strerror.argtypes = [C.c_int]
         for name in EXPORTS[1:]:
             getattr(_lib, name).restype = C.c_int
+        _lib.moe_res_vec_workspace_bytes.restype = C.c_size_t
     return _lib
 
 
@@ -119,6 +121,45 @@ def moe_predict_workload(s: MoeShape, h, res_vec, next_gate_w, next_gate_bias, p
                                              _ws_ptr(ws), _stream())
     _check(rc, "moe_predict_workload")
     return pred_counts, top_experts
+
+
+def moe_route_predict(s: MoeShape, h, gate_w, gate_bias, norm_mode: int, r, res_vec, next_gate_w, next_gate_bias, p: int,
+                      pred_counts, top_experts, ws: torch.Tensor):
+    rc = load_library().moe_route_predict(C.byref(s), _ptr(h, torch.bfloat16), _ptr(gate_w, torch.bfloat16),
+                                          _ptr(gate_bias, torch.float32), C.c_int(norm_mode), _ptr(r.topk_idx, torch.int32),
+                                          _ptr(r.topk_w, torch.float32), _ptr(r.counts, torch.int32),
+                                          _ptr(r.offsets, torch.int32), _ptr(r.perm, torch.int32),
+                                          _ptr(r.inv_perm, torch.int32), _ptr(res_vec, torch.float32),
+                                          _ptr(next_gate_w, torch.bfloat16), _ptr(next_gate_bias, torch.float32), C.c_int(p),
+                                          _ptr(pred_counts, torch.int32), _ptr(top_experts, torch.int32), _ws_ptr(ws), _stream())
+    _check(rc, "moe_route_predict")
+    return r
+
+
+class ResVecCalibration:
+    """Device buffers of one res_vec calibration: float64 running sum [d], scratch, token count."""
+
+    def __init__(self, d: int, device="cuda"):
+        lib = load_library()
+        self.d, self.n_total = d, 0
+        self.acc = torch.zeros(d, dtype=torch.float64, device=device)
+        self.ws = torch.empty(int(lib.moe_res_vec_workspace_bytes(C.c_int(d))), dtype=torch.uint8, device=device)
+        self.res_vec = torch.empty(d, dtype=torch.float32, device=device)
+
+    def accumulate(self, h_cur: torch.Tensor, h_next: torch.Tensor):
+        n = h_cur.shape[0]
+        assert h_cur.shape == h_next.shape == (n, self.d)
+        rc = load_library().moe_res_vec_accumulate(C.c_int(n), C.c_int(self.d), _ptr(h_cur, torch.bfloat16),
+                                                   _ptr(h_next, torch.bfloat16), _ptr(self.acc, torch.float64),
+                                                   C.c_void_p(self.ws.data_ptr()), _stream())
+        _check(rc, "moe_res_vec_accumulate")
+        self.n_total += n
+
+    def finish(self) -> torch.Tensor:
+        rc = load_library().moe_res_vec_finish(C.c_int(self.d), _ptr(self.acc, torch.float64), C.c_int64(self.n_total),
+                                               _ptr(self.res_vec, torch.float32), _stream())
+        _check(rc, "moe_res_vec_finish")
+        return self.res_vec
 
 
 def moe_expert_ffn(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, ws: torch.Tensor):

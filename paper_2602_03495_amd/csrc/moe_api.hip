@@ -15,6 +15,12 @@ int moe_combine_impl(const moe_shape *, const void *, const int32_t *, const flo
                      const void *, int, const float *, void *, hipStream_t);
 
 int moe_pack_weights_impl(int, int, int, const void *, void *, hipStream_t);
+int moe_route_predict_impl(const moe_shape *, const void *, const void *, const float *, int, int32_t *, float *, int32_t *,
+                           int32_t *, int32_t *, int32_t *, const float *, const void *, const float *, int, int32_t *, int32_t *,
+                           void *, hipStream_t);
+size_t moe_res_vec_ws_bytes(int);
+int moe_res_vec_accumulate_impl(int, int, const void *, const void *, double *, void *, hipStream_t);
+int moe_res_vec_finish_impl(int, const double *, long long, float *, hipStream_t);
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -75,6 +81,7 @@ int moe_predict_workload(const moe_shape *s, const void *h, const float *res_vec
     int rc = check_shape(s, true);
     if (rc != MOE_OK) return rc;
     if (!h || !res_vec || !next_gate_w || !pred_counts || !top_experts || !workspace) return MOE_EINVAL;
+    if (!aligned16(res_vec)) return MOE_EINVAL;
     if (!aligned16(h) || !aligned16(next_gate_w)) return MOE_EINVAL;
     if (p < 1 || p > s->N) return MOE_EINVAL;
     if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
@@ -142,6 +149,40 @@ int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *
     if (s == nullptr || s->T < 1 || s->d < 128 || s->d > 8192 || s->d % 128 != 0) return MOE_EINVAL;
     if (!h || !w_sg || !scale || !aligned16(h) || !aligned16(w_sg)) return MOE_EINVAL;
     return moe_shared_gate_impl(s, h, w_sg, scale, (hipStream_t)stream);
+}
+
+int moe_route_predict(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                      int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                      int32_t *inv_perm, const float *res_vec, const void *next_gate_w, const float *next_gate_bias,
+                      int p, int32_t *pred_counts, int32_t *top_experts, void *workspace, void *stream)
+{
+    int rc = check_shape(s, true);
+    if (rc != MOE_OK) return rc;
+    if (!h || !gate_w || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    if (!res_vec || !next_gate_w || !pred_counts || !top_experts || !workspace) return MOE_EINVAL;
+    if (!aligned16(h) || !aligned16(gate_w) || !aligned16(next_gate_w) || !aligned16(res_vec)) return MOE_EINVAL;
+    if (norm_mode != MOE_NORM_NONE && norm_mode != MOE_NORM_RENORM) return MOE_EINVAL;
+    if (p < 1 || p > s->N) return MOE_EINVAL;
+    if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    return moe_route_predict_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm, res_vec,
+                                  next_gate_w, next_gate_bias, p, pred_counts, top_experts, workspace, (hipStream_t)stream);
+}
+
+size_t moe_res_vec_workspace_bytes(int d) { return d > 0 ? moe_res_vec_ws_bytes(d) : 0; }
+
+int moe_res_vec_accumulate(int n, int d, const void *h_cur, const void *h_next, double *acc_sum, void *workspace,
+                           void *stream)
+{
+    if (n < 0 || d < 8 || d > 8192 || d % 8 != 0) return MOE_EINVAL;
+    if (!acc_sum || !workspace || ((uintptr_t)acc_sum & 7u) != 0 || ((uintptr_t)workspace & 7u) != 0) return MOE_EINVAL;
+    if (n > 0 && (!h_cur || !h_next || !aligned16(h_cur) || !aligned16(h_next))) return MOE_EINVAL;
+    return moe_res_vec_accumulate_impl(n, d, h_cur, h_next, acc_sum, workspace, (hipStream_t)stream);
+}
+
+int moe_res_vec_finish(int d, const double *acc_sum, int64_t n_total, float *res_vec, void *stream)
+{
+    if (d < 8 || d > 8192 || d % 8 != 0 || n_total < 1 || !acc_sum || !res_vec) return MOE_EINVAL;
+    return moe_res_vec_finish_impl(d, acc_sum, (long long)n_total, res_vec, (hipStream_t)stream);
 }
 
 }   // extern "C"

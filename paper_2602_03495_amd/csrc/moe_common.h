@@ -131,7 +131,7 @@ struct moe_ws_layout {
     size_t act;        // [T*k, I] bf16 inner activations
     size_t partial;    // [nsplit, T*k, d] fp32 split-K partial sums of the skinny down projection
     size_t sched;      // tile schedule of the tiled path
-    size_t route;      // routing scratch: folded bias [N], idx [T*k], w [T*k] (prediction), logits [16, N] (decode-sized gate)
+    size_t route;      // routing scratch: folded bias [N], idx [T*k], w [T*k] (prediction), 2 x logits [16, N] (decode-sized gates)
     size_t total;
 };
 
@@ -160,7 +160,7 @@ static inline moe_ws_layout moe_ws(const moe_shape *s)
     L.sched = off;
     off += moe_align256(((size_t)R / MOE_TILE_M + MOE_MAX_EXPERTS + 8) * 16);
     L.route = off;
-    off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4) + moe_align256(16 * MOE_MAX_EXPERTS * 4);
+    off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4) + 2 * moe_align256(16 * MOE_MAX_EXPERTS * 4);
     L.total = off;
     return L;
 }

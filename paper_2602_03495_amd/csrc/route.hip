@@ -16,16 +16,87 @@
 #define ROUTE_THREADS 512
 #define ROUTE_WAVES 8
 
-// ---------------------------------------------------------------------------------------------------
-template <int NT>   // NT = ceil(N / 16) expert tiles
-__global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
-    int T, int d, int N, int k, const uint16_t *__restrict__ h, const uint16_t *__restrict__ gate_w,
-    const float *__restrict__ bias, int norm_mode, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w,
-    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv_perm,   // non-null counts: single-block launch that also does histogram, scan and permutation
-    const float *__restrict__ logits_in,   // non-null: skip the gate product, select from these [T,N] logits
-    float *__restrict__ logits_out)        // non-null: only compute logits of experts 16*NT*blockIdx.y .. and store them [T,N]
+// res_vec . W[e,:] over one wavefront: lane l takes the 8-element groups at 8l + 512m (d is a multiple of 128, so a
+// group is whole or absent), each group accumulated in element order onto the lane's sum; the 64 partial sums are
+// added by butterfly.  One definition for every caller, so the folded bias does not depend on the batch size.
+__device__ __forceinline__ float residual_dot(int d, const float *__restrict__ res_vec, const uint16_t *__restrict__ w, int lane)
 {
+    float acc = 0.f;
+    for (int j = lane * 8; j < d; j += 512) {
+        const u32x4 pr = *reinterpret_cast<const u32x4 *>(w + j);
+        const float4 r0 = *reinterpret_cast<const float4 *>(res_vec + j);
+        const float4 r1 = *reinterpret_cast<const float4 *>(res_vec + j + 4);
+        acc = fmaf(r0.x, bf16_lo(pr[0]), acc);
+        acc = fmaf(r0.y, bf16_hi(pr[0]), acc);
+        acc = fmaf(r0.z, bf16_lo(pr[1]), acc);
+        acc = fmaf(r0.w, bf16_hi(pr[1]), acc);
+        acc = fmaf(r1.x, bf16_lo(pr[2]), acc);
+        acc = fmaf(r1.y, bf16_hi(pr[2]), acc);
+        acc = fmaf(r1.z, bf16_lo(pr[3]), acc);
+        acc = fmaf(r1.w, bf16_hi(pr[3]), acc);
+    }
+    return wave_sum(acc);
+}
+
+// The p largest workloads by descending value, equal values by ascending index; one wavefront, lane l holding the
+// workloads c0 of expert l and c1 of expert l + 64.
+__device__ __forceinline__ void top_p_of(int c0, int c1, int N, int p, int32_t *__restrict__ top, int lane)
+{
+    if (lane >= N) c0 = -1;
+    if (lane + 64 >= N) c1 = -1;
+    for (int s = 0; s < p; ++s) {
+        int bc, bi;
+        if (c0 >= c1) { bc = c0; bi = lane; } else { bc = c1; bi = lane + 64; }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            int oc = __shfl_xor(bc, o, MOE_WAVE);
+            int oi = __shfl_xor(bi, o, MOE_WAVE);
+            if (oc > bc || (oc == bc && oi < bi)) { bc = oc; bi = oi; }
+        }
+        if (bi == lane) c0 = -1;
+        if (bi == lane + 64) c1 = -1;
+        if (lane == 0) top[s] = bi;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// One gate to evaluate: the layer's own (routing) or the next layer's (prediction).  A launch carries two jobs and
+// blockIdx.z picks one, so that a decode step can route and predict in the same pair of launches.
+struct gate_job {
+    const uint16_t *gate_w;    // [N,d] bf16
+    const float *bias;         // [N] or null
+    const float *res_vec;      // non-null (decode-sized launches only): add res_vec . W[e] to the bias of expert e
+    int norm_mode;
+    int32_t *topk_idx;         // [T,k]
+    float *topk_w;             // [T,k]
+    int32_t *counts;           // non-null: single-block launch that also does the histogram (and, with perm, scan and permutation)
+    int32_t *offsets, *perm, *inv_perm;
+    const float *logits_in;    // non-null: skip the gate product, select from these [T,N] logits
+    float *logits_out;         // non-null: only compute the logits of experts 16*NT*blockIdx.y .. and store them [T,N]
+    int32_t *top;              // with counts and without perm: the p largest workloads
+    int p;
+};
+
+template <int NT>   // NT = ceil(N / 16) expert tiles
+__global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, int N, int k, const uint16_t *__restrict__ h,
+                                                                  gate_job job0, gate_job job1)
+{
+    const gate_job &J = blockIdx.z == 0 ? job0 : job1;
+    const uint16_t *__restrict__ gate_w = J.gate_w;
+    const float *__restrict__ bias = J.bias;
+    const float *__restrict__ res_vec = J.res_vec;
+    const int norm_mode = J.norm_mode;
+    int32_t *__restrict__ topk_idx = J.topk_idx;
+    float *__restrict__ topk_w = J.topk_w;
+    int32_t *__restrict__ counts = J.counts;
+    int32_t *__restrict__ offsets = J.offsets;
+    int32_t *__restrict__ perm = J.perm;
+    int32_t *__restrict__ inv_perm = J.inv_perm;
+    const float *__restrict__ logits_in = J.logits_in;
+    float *__restrict__ logits_out = J.logits_out;
+    int32_t *__restrict__ top = J.top;
+    const int p = J.p;
+
     constexpr int NP = NT * 16;                       // padded expert count
     __shared__ float part[ROUTE_WAVES][ROUTE_TOKENS][NP + 1];   // per-wave partial logits
     __shared__ __attribute__((aligned(16))) float lg[ROUTE_TOKENS][NP + 4];   // reduced logits (+bias), rows 16-byte aligned
@@ -78,20 +149,36 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
         }
     }
+    // bias of the block's experts, with the residual vector folded in: (h + res_vec).W + b = h.W + (res_vec.W + b)
+    __shared__ float bias_s[NP];
+    if (logits_in == nullptr) {
+        for (int el = wave; el < NP; el += ROUTE_WAVES) {
+            const int e = e_base + el;
+            float b = 0.f;
+            if (e < N) {
+                b = bias != nullptr ? bias[e] : 0.f;
+                if (res_vec != nullptr) b = residual_dot(d, res_vec, gate_w + (size_t)e * d, lane) + b;
+            }
+            if (lane == 0) bias_s[el] = b;
+        }
+    }
+    if (logits_in == nullptr) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            part[wave][4 * g + r][nt * 16 + i] = acc[nt][r];
+            for (int r = 0; r < 4; ++r)
+                part[wave][4 * g + r][nt * 16 + i] = acc[nt][r];
+    }
     __syncthreads();
     for (int idx = threadIdx.x; idx < ROUTE_TOKENS * NP; idx += ROUTE_THREADS) {
         int tt = idx / NP, e = idx % NP;
-        float v = ((part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e])) +
-                  ((part[4][tt][e] + part[5][tt][e]) + (part[6][tt][e] + part[7][tt][e]));
+        float v;
         if (logits_in != nullptr) {
             v = (t0 + tt < T && e < N) ? logits_in[(size_t)(t0 + tt) * N + e] : 0.f;
-        } else if (bias != nullptr && e_base + e < N) {
-            v += bias[e_base + e];
+        } else {
+            v = ((part[0][tt][e] + part[1][tt][e]) + (part[2][tt][e] + part[3][tt][e])) +
+                ((part[4][tt][e] + part[5][tt][e]) + (part[6][tt][e] + part[7][tt][e]));
+            if (e_base + e < N) v += bias_s[e];
         }
         if (logits_out != nullptr) {
             if (t0 + tt < T && e_base + e < N) logits_out[(size_t)(t0 + tt) * N + e_base + e] = v;
@@ -146,35 +233,53 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(
     }
     if (counts == nullptr) return;
 
-    // ---- decode-sized batch (one block, T*k <= 128): histogram, scan and stable permutation right here ----
-    __shared__ int hist[MOE_MAX_EXPERTS + 1];
-    int *sel_idx = reinterpret_cast<int *>(&part[0][0][0]);      // the partial-logit scratch is free again
+    // ---- decode-sized batch (one block, T <= 16): histogram, scan and stable permutation right here ----------
+    // A token selects an expert at most once, so the rows of expert e are one per selecting token, in token order:
+    // a 16-bit token mask per expert gives the workload (its popcount) and the rank of a row within its expert (the
+    // popcount below the token's bit) without any serial pass.
+    __shared__ unsigned tokmask[MOE_MAX_EXPERTS];
+    __shared__ int off_s[MOE_MAX_EXPERTS];
+    const int *sel_idx = reinterpret_cast<const int *>(&part[0][0][0]);      // the partial-logit scratch is free again
     const int R = T * k;
-    if (threadIdx.x <= MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
+    if (threadIdx.x < MOE_MAX_EXPERTS) tokmask[threadIdx.x] = 0u;
     __syncthreads();
-    int my_e = -1, rank = 0;
+    int my_e = -1, my_t = 0;
     if ((int)threadIdx.x < R) {
         my_e = sel_idx[threadIdx.x];
-        atomicAdd(&hist[my_e], 1);
-        for (int r = 0; r < (int)threadIdx.x; ++r) rank += sel_idx[r] == my_e;   // rows of the same expert before this one
+        my_t = threadIdx.x / k;
+        atomicOr(&tokmask[my_e], 1u << my_t);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int j = 0; j < N; ++j) {
-            const int c = hist[j];
-            counts[j] = c;
-            offsets[j] = run;
-            hist[j] = run;
-            run += c;
+    if (wave == 0) {
+        // workloads of experts lane and lane + 64, and their exclusive prefix sums over all 128 slots
+        const int c0 = lane < N ? __popc(tokmask[lane]) : 0;
+        const int c1 = lane + 64 < N ? __popc(tokmask[lane + 64]) : 0;
+        int s0 = c0, s1 = c1;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u0 = __shfl_up(s0, o, MOE_WAVE), u1 = __shfl_up(s1, o, MOE_WAVE);
+            if (lane >= o) { s0 += u0; s1 += u1; }
         }
-        offsets[N] = run;
+        const int tot0 = __shfl(s0, 63, MOE_WAVE);
+        if (lane < N) counts[lane] = c0;
+        if (lane + 64 < N) counts[lane + 64] = c1;
+        if (perm == nullptr) {
+            // prediction: the workloads and the p largest of them (equal workloads by ascending index)
+            top_p_of(c0, c1, N, p, top, lane);
+        } else {
+            off_s[lane] = s0 - c0;
+            off_s[lane + 64] = tot0 + s1 - c1;
+            if (lane < N) offsets[lane] = s0 - c0;
+            if (lane + 64 < N) offsets[lane + 64] = tot0 + s1 - c1;
+            if (lane == 0) offsets[N] = R;
+        }
     }
+    if (perm == nullptr) return;
     __syncthreads();
     if ((int)threadIdx.x < R) {
-        const int p = hist[my_e] + rank;
-        perm[p] = threadIdx.x;
-        inv_perm[threadIdx.x] = p;
+        const int pos = off_s[my_e] + __popc(tokmask[my_e] & ((1u << my_t) - 1u));
+        perm[pos] = threadIdx.x;
+        inv_perm[threadIdx.x] = pos;
     }
 }
 
@@ -272,14 +377,7 @@ __global__ __launch_bounds__(64) void fold_residual_kernel(int d, const float *_
                                                            const float *__restrict__ bias, float *__restrict__ bias_out)
 {
     const int e = blockIdx.x, lane = threadIdx.x;
-    const uint16_t *w = gate_w + (size_t)e * d;
-    float acc = 0.f;
-    for (int j = lane * 2; j < d; j += 128) {
-        uint32_t pr = *reinterpret_cast<const uint32_t *>(w + j);
-        acc = fmaf(res_vec[j], bf16_lo(pr), acc);
-        acc = fmaf(res_vec[j + 1], bf16_hi(pr), acc);
-    }
-    acc = wave_sum(acc);
+    const float acc = residual_dot(d, res_vec, gate_w + (size_t)e * d, lane);
     if (lane == 0) bias_out[e] = acc + (bias != nullptr ? bias[e] : 0.f);
 }
 
@@ -292,24 +390,7 @@ __global__ __launch_bounds__(256) void hist_top_kernel(int R, int N, int p, cons
     for (int r = threadIdx.x; r < R; r += 256) atomicAdd(&hist[idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
     __syncthreads();
     if (threadIdx.x < N) pred_counts[threadIdx.x] = hist[threadIdx.x];
-    if (threadIdx.x < 64) {
-        const int lane = threadIdx.x;
-        int c0 = lane < N ? hist[lane] : -1;
-        int c1 = lane + 64 < N ? hist[lane + 64] : -1;
-        for (int s = 0; s < p; ++s) {
-            int bc, bi;
-            if (c0 >= c1) { bc = c0; bi = lane; } else { bc = c1; bi = lane + 64; }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                int oc = __shfl_xor(bc, o, MOE_WAVE);
-                int oi = __shfl_xor(bi, o, MOE_WAVE);
-                if (oc > bc || (oc == bc && oi < bi)) { bc = oc; bi = oi; }
-            }
-            if (bi == lane) c0 = -1;
-            if (bi == lane + 64) c1 = -1;
-            if (lane == 0) top[s] = bi;
-        }
-    }
+    if (threadIdx.x < 64) top_p_of(hist[threadIdx.x], hist[threadIdx.x + 64], N, p, top, threadIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -347,27 +428,42 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const ui
 
 // ---------------------------------------------------------------------------------------------------
 // host side
-static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_w, const float *bias, int norm_mode,
-                            int32_t *topk_idx, float *topk_w, hipStream_t st, float *ws_logits, int32_t *counts = nullptr,
-                            int32_t *offsets = nullptr, int32_t *perm = nullptr, int32_t *inv_perm = nullptr)
+static gate_job make_job(const void *gate_w, const float *bias, int norm_mode, int32_t *topk_idx, float *topk_w)
+{
+    gate_job j = {};
+    j.gate_w = (const uint16_t *)gate_w;
+    j.bias = bias;
+    j.norm_mode = norm_mode;
+    j.topk_idx = topk_idx;
+    j.topk_w = topk_w;
+    return j;
+}
+
+// Launches the gate kernels for one job, or for two jobs side by side (decode-sized batches only: both then take the
+// same path).  ws_logits[i]: [16, N] scratch of job i for the split decode path, or null.
+static int launch_gate_topk(const moe_shape *s, const void *h, hipStream_t st, int n_jobs, gate_job *jobs, float *const *ws_logits)
 {
     const int NT = (s->N + 15) / 16;
-    dim3 grid((s->T + ROUTE_TOKENS - 1) / ROUTE_TOKENS), block(ROUTE_THREADS);
-    const uint16_t *hp = (const uint16_t *)h, *wp = (const uint16_t *)gate_w;
-    const float *lin = nullptr;
-    if (s->T <= ROUTE_TOKENS && NT >= 2 && ws_logits != nullptr) {
+    dim3 grid((s->T + ROUTE_TOKENS - 1) / ROUTE_TOKENS, 1, n_jobs), block(ROUTE_THREADS);
+    const uint16_t *hp = (const uint16_t *)h;
+    gate_job sel[2] = {jobs[0], jobs[n_jobs - 1]};
+    if (s->T <= ROUTE_TOKENS && NT >= 2 && ws_logits[0] != nullptr) {
         // decode-sized batch with many experts: one block would stream the whole gate matrix alone, so the gate
         // product is spread over one block per 16 experts and the selection runs from the stored logits
-        hipLaunchKernelGGL(gate_topk_kernel<1>, dim3(1, NT), block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode,
-                           (int32_t *)nullptr, (float *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
-                           (int32_t *)nullptr, (const float *)nullptr, ws_logits);
+        gate_job lg[2];
+        for (int i = 0; i < 2; ++i) {
+            const int ji = i < n_jobs ? i : n_jobs - 1;
+            lg[i] = make_job(jobs[ji].gate_w, jobs[ji].bias, jobs[ji].norm_mode, nullptr, nullptr);
+            lg[i].res_vec = jobs[ji].res_vec;
+            lg[i].logits_out = ws_logits[ji];
+            sel[i].logits_in = ws_logits[ji];
+        }
+        hipLaunchKernelGGL(gate_topk_kernel<1>, dim3(1, NT, n_jobs), block, 0, st, s->T, s->d, s->N, s->k, hp, lg[0], lg[1]);
         MOE_CHECK_LAUNCH();
-        lin = ws_logits;
     }
-#define GT(n)                                                                                                       \
-    case n:                                                                                                         \
-        hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, wp, bias, norm_mode, \
-                           topk_idx, topk_w, counts, offsets, perm, inv_perm, lin, (float *)nullptr);               \
+#define GT(n)                                                                                                  \
+    case n:                                                                                                    \
+        hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, sel[0], sel[1]); \
         break;
     switch (NT) {
         GT(1) GT(2) GT(3) GT(4) GT(5) GT(6) GT(7) GT(8)
@@ -379,22 +475,55 @@ static int launch_gate_topk(const moe_shape *s, const void *h, const void *gate_
     return MOE_OK;
 }
 
-static float *route_logits_scratch(const moe_shape *s, void *workspace)
+// [16, N] fp32 logits scratch number `which` (0: routing, 1: prediction) inside the routing workspace
+static float *route_logits_scratch(const moe_shape *s, void *workspace, int which)
 {
     if (workspace == nullptr) return nullptr;
     moe_ws_layout L = moe_ws(s);
-    return (float *)((char *)workspace + L.route + moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256((size_t)s->T * s->k * 4));
+    return (float *)((char *)workspace + L.route + moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256((size_t)s->T * s->k * 4) +
+                     (size_t)which * moe_align256(16 * MOE_MAX_EXPERTS * 4));
+}
+
+static bool single_block_routing(const moe_shape *s) { return s->T <= ROUTE_TOKENS && s->T * s->k <= 128; }
+
+static gate_job route_job(const moe_shape *s, const void *gate_w, const float *gate_bias, int norm_mode, int32_t *topk_idx,
+                          float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm)
+{
+    gate_job j = make_job(gate_w, gate_bias, norm_mode, topk_idx, topk_w);
+    if (single_block_routing(s)) {     // one block: histogram, scan and permutation in the same launch
+        j.counts = counts;
+        j.offsets = offsets;
+        j.perm = perm;
+        j.inv_perm = inv_perm;
+    }
+    return j;
+}
+
+// prediction job of a decode-sized batch: residual folded inside the gate kernel, histogram and top-p in the selecting block
+static gate_job predict_job(const moe_shape *s, const float *res_vec, const void *next_gate_w, const float *next_gate_bias, int p,
+                            int32_t *pred_counts, int32_t *top_experts, void *workspace)
+{
+    moe_ws_layout L = moe_ws(s);
+    char *ws = (char *)workspace + L.route;
+    const size_t R = (size_t)s->T * s->k;
+    int32_t *idx = (int32_t *)(ws + moe_align256(MOE_MAX_EXPERTS * 4));
+    float *w = (float *)(ws + moe_align256(MOE_MAX_EXPERTS * 4) + moe_align256(R * 4));
+    gate_job j = make_job(next_gate_w, next_gate_bias, MOE_NORM_NONE, idx, w);
+    j.res_vec = res_vec;
+    j.counts = pred_counts;
+    j.top = top_experts;
+    j.p = p;
+    return j;
 }
 
 int moe_route_impl(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
                    int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
                    int32_t *inv_perm, void *workspace, hipStream_t st)
 {
-    float *wl = route_logits_scratch(s, workspace);
-    if (s->T <= ROUTE_TOKENS && s->T * s->k <= 128)      // one block: everything in a single launch
-        return launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, wl, counts, offsets, perm, inv_perm);
-    int rc = launch_gate_topk(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, st, wl);
-    if (rc != MOE_OK) return rc;
+    gate_job j = route_job(s, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm);
+    float *wl[1] = {route_logits_scratch(s, workspace, 0)};
+    int rc = launch_gate_topk(s, h, st, 1, &j, wl);
+    if (rc != MOE_OK || single_block_routing(s)) return rc;
     hipLaunchKernelGGL(hist_scan_perm_kernel, dim3(s->N), dim3(256), 0, st, s->T * s->k, s->N, topk_idx, counts,
                        offsets, perm, inv_perm);
     MOE_CHECK_LAUNCH();
@@ -405,6 +534,11 @@ int moe_predict_impl(const moe_shape *s, const void *h, const float *res_vec, co
                      const float *next_gate_bias, int p, int32_t *pred_counts, int32_t *top_experts, void *workspace,
                      hipStream_t st)
 {
+    if (single_block_routing(s)) {
+        gate_job j = predict_job(s, res_vec, next_gate_w, next_gate_bias, p, pred_counts, top_experts, workspace);
+        float *wl[1] = {route_logits_scratch(s, workspace, 1)};
+        return launch_gate_topk(s, h, st, 1, &j, wl);
+    }
     moe_ws_layout L = moe_ws(s);
     char *ws = (char *)workspace + L.route;
     float *bias2 = (float *)ws;
@@ -414,11 +548,31 @@ int moe_predict_impl(const moe_shape *s, const void *h, const float *res_vec, co
     hipLaunchKernelGGL(fold_residual_kernel, dim3(s->N), dim3(64), 0, st, s->d, res_vec, (const uint16_t *)next_gate_w,
                        next_gate_bias, bias2);
     MOE_CHECK_LAUNCH();
-    int rc = launch_gate_topk(s, h, next_gate_w, bias2, MOE_NORM_NONE, idx, w, st, route_logits_scratch(s, workspace));
+    gate_job j = make_job(next_gate_w, bias2, MOE_NORM_NONE, idx, w);
+    float *wl[1] = {route_logits_scratch(s, workspace, 1)};
+    int rc = launch_gate_topk(s, h, st, 1, &j, wl);
     if (rc != MOE_OK) return rc;
     hipLaunchKernelGGL(hist_top_kernel, dim3(1), dim3(256), 0, st, (int)R, s->N, p, idx, pred_counts, top_experts);
     MOE_CHECK_LAUNCH();
     return MOE_OK;
+}
+
+// Routing of this layer and workload prediction of the next in one pass: at decode sizes the two gates are
+// evaluated by the same two launches (blockIdx.z = 0 routes, 1 predicts); larger batches run one after the other.
+int moe_route_predict_impl(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                           int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                           int32_t *inv_perm, const float *res_vec, const void *next_gate_w, const float *next_gate_bias,
+                           int p, int32_t *pred_counts, int32_t *top_experts, void *workspace, hipStream_t st)
+{
+    if (!single_block_routing(s)) {
+        int rc = moe_route_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace, st);
+        if (rc != MOE_OK) return rc;
+        return moe_predict_impl(s, h, res_vec, next_gate_w, next_gate_bias, p, pred_counts, top_experts, workspace, st);
+    }
+    gate_job jobs[2] = {route_job(s, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm),
+                        predict_job(s, res_vec, next_gate_w, next_gate_bias, p, pred_counts, top_experts, workspace)};
+    float *wl[2] = {route_logits_scratch(s, workspace, 0), route_logits_scratch(s, workspace, 1)};
+    return launch_gate_topk(s, h, st, 2, jobs, wl);
 }
 
 int moe_dense_route_impl(const moe_shape *s, int32_t *counts, int32_t *offsets, int32_t *perm, hipStream_t st)

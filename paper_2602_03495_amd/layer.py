@@ -80,6 +80,13 @@ class MoeLayer:
         b = w.gate_bias if bias is None else bias
         return B.moe_route(self.shape, h, w.gate_w, b, self.cfg.norm_mode, self.routing, self.ws)
 
+    def route_predict(self, h, w: LayerWeights, res_vec, next_w: LayerWeights, p: int, top_experts, bias=None, next_bias=None):
+        """Routing of this layer and workload prediction of the next in one call."""
+        b = w.gate_bias if bias is None else bias
+        nb = next_w.gate_bias if next_bias is None else next_bias
+        return B.moe_route_predict(self.shape, h, w.gate_w, b, self.cfg.norm_mode, self.routing, res_vec, next_w.gate_w, nb, p,
+                                   self.pred_counts, top_experts, self.ws)
+
     def expert_ffn(self, h, w: LayerWeights, mask):
         r = self.routing
         return B.moe_expert_ffn(self.shape, h, r.perm, r.offsets, r.counts, w.w1, w.w3, w.w2, mask, self.y, self.ws)
@@ -105,6 +112,8 @@ class MoeLayer:
             self.shared_ffn(h, w)
         return self.combine(mask, with_shared)
 
-    def predict(self, h, res_vec, next_w: LayerWeights, p: int, top_experts, next_bias=None):
+    def predict(self, h, res_vec, next_w: LayerWeights, p: int, top_experts, next_bias=None, ws=None):
+        """ws: a workspace of its own when the prediction runs concurrently with this layer's other calls."""
         b = next_w.gate_bias if next_bias is None else next_bias
-        return B.moe_predict_workload(self.shape, h, res_vec, next_w.gate_w, b, p, self.pred_counts, top_experts, self.ws)
+        return B.moe_predict_workload(self.shape, h, res_vec, next_w.gate_w, b, p, self.pred_counts, top_experts,
+                                      self.ws if ws is None else ws)

@@ -54,6 +54,7 @@ class DecodeStack:
         self.layer = Lm.MoeLayer(cfg, T)
         self.res_vec = [torch.zeros(cfg.d, dtype=torch.float32, device=device) for _ in range(n_layers)]
         self.top = torch.empty(8, dtype=torch.int32, device=device)
+        self.pred_ws = B.alloc_workspace(self.layer.shape, device)   # scratch of a prediction that overlaps routing
 
     def bias_paths(self, steps: int) -> torch.Tensor:
         """[layers, steps, N] fp32 AR(1) gate-bias paths, on the device."""
@@ -64,19 +65,26 @@ class DecodeStack:
         """res_vec^(l) = mean over calibration tokens of h^(l+1) - h^(l) (the paper's res_vec equation), from
         `steps` batches that are not part of the measured run."""
         cfg, L = self.cfg, self.layer
-        acc = [torch.zeros(cfg.d, dtype=torch.float64, device="cuda") for _ in range(self.n_layers)]
+        cal = [B.ResVecCalibration(cfg.d) for _ in range(self.n_layers)]
         for t in range(steps):
             h = Lm.to_device_bf16(wl.hidden_states(cfg, self.T, draw=100000 + t))
             for l in range(self.n_layers):
                 out = L.forward(h, self.weights[l], None, bias=bias[l, t % bias.shape[1]].contiguous())
                 h_next = next_hidden(h, out)
-                acc[l] += (h_next.double() - h.double()).sum(0)
+                cal[l].accumulate(h, h_next)
                 h = h_next
         for l in range(self.n_layers):
-            self.res_vec[l] = (acc[l] / (steps * self.T)).float()
+            self.res_vec[l] = cal[l].finish()
 
-    def run(self, steps: int, bias: torch.Tensor, use_res_vec: bool = True, p_list=(1, 4, 8)) -> StackResult:
+    def run(self, steps: int, bias: torch.Tensor, use_res_vec: bool = True, p_list=(1, 4, 8),
+            predict: str = "fused") -> StackResult:
+        """predict: "fused" routes and predicts with one call (moe_route_predict); "inline" issues the prediction between routing and the expert FFN on the same stream; "side"
+        issues it on a second stream of the same priority, concurrent with routing, FFN and combine, and joins it
+        before the layer ends (the separate work stream of the paper's system overview); "off" skips it."""
         cfg, L, nl = self.cfg, self.layer, self.n_layers
+        assert predict in ("fused", "inline", "side", "off")
+        side = torch.cuda.Stream() if predict == "side" else None
+        main = torch.cuda.current_stream()
         counts = torch.zeros((steps, nl, cfg.N), dtype=torch.int32, device="cuda")
         preds = torch.zeros((steps, max(nl - 1, 1), cfg.N), dtype=torch.int32, device="cuda")
         masks = [torch.ones(cfg.N, dtype=torch.uint8, device="cuda") for _ in range(nl)]
@@ -88,18 +96,29 @@ class DecodeStack:
             for l in range(nl):
                 w = self.weights[l]
                 b = bias[l, t].contiguous()
+                nb = bias[l + 1, t].contiguous() if l + 1 < nl else None
+                rv = self.res_vec[l] if use_res_vec else zero_rv
+                do_pred = l + 1 < nl and predict != "off"
                 e0.record()
-                L.route(h, w, b)
-                if l + 1 < nl:
-                    L.predict(h, self.res_vec[l] if use_res_vec else zero_rv, self.weights[l + 1], 8, self.top,
-                              next_bias=bias[l + 1, t].contiguous())
+                if do_pred and side is not None:
+                    side.wait_stream(main)
+                    with torch.cuda.stream(side):
+                        L.predict(h, rv, self.weights[l + 1], 8, self.top, next_bias=nb, ws=self.pred_ws)
+                if do_pred and predict == "fused":
+                    L.route_predict(h, w, rv, self.weights[l + 1], 8, self.top, bias=b, next_bias=nb)
+                else:
+                    L.route(h, w, b)
+                    if do_pred and predict == "inline":
+                        L.predict(h, rv, self.weights[l + 1], 8, self.top, next_bias=nb)
                 L.expert_ffn(h, w, masks[l])
                 out = L.combine(masks[l])
+                if do_pred and side is not None:
+                    main.wait_stream(side)
                 e1.record()
                 e1.synchronize()
                 total_ms += e0.elapsed_time(e1)
                 counts[t, l] = L.routing.counts
-                if l + 1 < nl:
+                if do_pred:
                     preds[t, l] = L.pred_counts
                 # next step's mask of this layer: the half of the experts with the largest workloads now
                 order = torch.sort(L.routing.counts.to(torch.int64) * cfg.N + (cfg.N - 1 - torch.arange(cfg.N, device="cuda")),
@@ -111,6 +130,55 @@ class DecodeStack:
         c, pr = counts.cpu().numpy(), preds.cpu().numpy()
         res = StackResult(c, pr, total_ms * 1e-3, self.T * steps / (total_ms * 1e-3))
         for p in p_list:
-            if nl > 1:
+            if nl > 1 and predict != "off":
                 res.acc[p] = float(np.mean([top_p_accuracy(pr[t, l], c[t, l + 1], p) for t in range(steps) for l in range(nl - 1)]))
         return res
+
+
+    def layer_graph_seconds(self, bias: torch.Tensor, predict: str = "fused", layer: int = 0, replays: int = 200) -> float:
+        """One layer pass (route, prediction of the next layer, masked expert FFN, combine) captured in a HIP graph and
+        replayed: seconds per replay, without the host's per-launch cost.  predict = "side" forks the prediction onto a
+        second stream inside the graph, so it may run next to the other three calls."""
+        import time
+        assert predict in ("fused", "inline", "side", "off") and layer + 1 < self.n_layers
+        cfg, L = self.cfg, self.layer
+        w, wn = self.weights[layer], self.weights[layer + 1]
+        h = Lm.to_device_bf16(wl.hidden_states(cfg, self.T, draw=0))
+        b, nb = bias[layer, 0].contiguous(), bias[layer + 1, 0].contiguous()
+        L.route(h, w, b)
+        torch.cuda.synchronize()
+        mask = torch.from_numpy(wl.mask_top_by_counts(L.routing.counts.cpu().numpy(), cfg.N // 2)).cuda()
+        rv = self.res_vec[layer]
+
+        def one_pass(cap: torch.cuda.Stream, side: Optional[torch.cuda.Stream]):
+            if predict == "side":
+                side.wait_stream(cap)
+                with torch.cuda.stream(side):
+                    L.predict(h, rv, wn, 8, self.top, next_bias=nb, ws=self.pred_ws)
+            if predict == "fused":
+                L.route_predict(h, w, rv, wn, 8, self.top, bias=b, next_bias=nb)
+            else:
+                L.route(h, w, b)
+                if predict == "inline":
+                    L.predict(h, rv, wn, 8, self.top, next_bias=nb)
+            L.expert_ffn(h, w, mask)
+            L.combine(mask)
+            if predict == "side":
+                cap.wait_stream(side)
+
+        cap, side = torch.cuda.Stream(), torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            one_pass(cap, side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            one_pass(cap, side)
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / replays

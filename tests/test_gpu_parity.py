@@ -260,3 +260,68 @@ def test_predict_workload(gpu, name, T, p):
     assert np.array_equal(_np(top), oracle.top_p(g_cnt, p))
     if nex == 0:
         assert np.array_equal(_np(top), o_top)
+
+
+@pytest.mark.parametrize("d,batches", [(256, [1000, 37]), (2048, [4097]), (384, [1, 0, 63, 64, 65]), (8, [5000])])
+def test_res_vec_calibration_matches_oracle(gpu, d, batches):
+    # device reduction of the res_vec equation over a calibration set that arrives in batches, against the
+    # oracle on the concatenated set.  Both sum exactly representable bf16 differences in float64 (the orders
+    # differ, the sums stay far below 2^53 ulps of the smallest term), so the fp32 results agree to the last bit
+    # or, where the float64 sums differ in their last bits at a rounding boundary, to one fp32 ulp.
+    B, Lm = gpu
+    print(f"res_vec calibration d={d} batches={batches}", flush=True)
+    cfg = wl.scaled(wl.CONFIGS["tiny"], d=max(d, 128))
+    cal = B.ResVecCalibration(d)
+    cur, nxt = [], []
+    for i, n in enumerate(batches):
+        if n == 0:
+            h0 = np.zeros((0, d), np.uint16)
+            h1 = np.zeros((0, d), np.uint16)
+        else:
+            h0 = np.ascontiguousarray(wl.hidden_states(cfg, n, draw=50 + i)[:, :d])
+            h1 = np.ascontiguousarray(wl.next_hidden_states(cfg, wl.hidden_states(cfg, n, draw=50 + i), draw=i)[:, :d])
+        cur.append(h0)
+        nxt.append(h1)
+        if n:
+            cal.accumulate(Lm.to_device_bf16(h0), Lm.to_device_bf16(h1))
+        else:
+            cal.accumulate(torch.empty((0, d), dtype=torch.bfloat16, device="cuda"),
+                           torch.empty((0, d), dtype=torch.bfloat16, device="cuda"))
+    got = cal.finish().cpu().numpy()
+    ref = oracle.res_vec(np.concatenate(cur), np.concatenate(nxt))
+    assert cal.n_total == sum(batches)
+    ulp = np.spacing(np.abs(ref).astype(np.float32))
+    assert np.all(np.abs(got - ref) <= ulp), float(np.abs(got - ref).max())
+    assert np.mean(got == ref) > 0.99
+    assert np.abs(ref).max() > 0     # the drift of the generator is not zero: the comparison is not vacuous
+
+
+@pytest.mark.parametrize("name,T", [("tiny", 16), ("mixtral_s", 16), ("qwen3_s", 16), ("qwen3_s", 7), ("deepseek_s", 1),
+                                    ("qwen15_s", 40), ("qwen3_s", 300)])
+def test_route_predict_equals_the_two_calls(gpu, name, T):
+    # one call that routes this layer and predicts the next must give exactly what moe_route followed by
+    # moe_predict_workload gives (both are checked against the oracle elsewhere), at decode sizes, where the two gates
+    # share their launches, and beyond
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"route_predict {name} T={T}", flush=True)
+    p = min(8, cfg.N)
+    h = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=3))
+    W0, b0 = Lm.to_device_bf16(wl.gate_weights(cfg, 0)), torch.from_numpy(wl.gate_bias(cfg, 0)).cuda()
+    W1, b1 = Lm.to_device_bf16(wl.gate_weights(cfg, 1)), torch.from_numpy(wl.gate_bias(cfg, 1)).cuda()
+    rv = torch.from_numpy(wl.layer_drift(cfg)).cuda()
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    ws = B.alloc_workspace(s)
+    ra, rb = B.alloc_routing(s), B.alloc_routing(s)
+    pca, pcb = (torch.full((cfg.N,), -1, dtype=torch.int32, device="cuda") for _ in range(2))
+    topa, topb = (torch.full((p,), -1, dtype=torch.int32, device="cuda") for _ in range(2))
+    B.moe_route(s, h, W0, b0, cfg.norm_mode, ra, ws)
+    B.moe_predict_workload(s, h, rv, W1, b1, p, pca, topa, ws)
+    torch.cuda.synchronize()
+    ws.zero_()
+    B.moe_route_predict(s, h, W0, b0, cfg.norm_mode, rb, rv, W1, b1, p, pcb, topb, ws)
+    torch.cuda.synchronize()
+    for f in ("topk_idx", "topk_w", "counts", "offsets", "perm", "inv_perm"):
+        assert torch.equal(getattr(ra, f), getattr(rb, f)), f
+    assert torch.equal(pca, pcb) and torch.equal(topa, topb)
+    assert int(pcb.sum()) == T * cfg.k and int(rb.counts.sum()) == T * cfg.k

@@ -56,3 +56,17 @@ def test_stack_calibrated_residual_does_not_hurt(stack):
     without = st.run(steps, bias, use_res_vec=False)
     l1 = lambda r: np.abs(r.pred_counts[:, :2].astype(np.int64) - r.counts[:, 1:]).sum()
     assert l1(with_rv) <= 1.1 * l1(without) + 8
+
+
+def test_prediction_on_a_side_stream_gives_the_same_results(stack):
+    # the prediction issued on a second stream, concurrent with routing / FFN / combine and with a workspace of its
+    # own, must change neither the layer results nor the predictions
+    cfg, st = stack
+    steps = 5
+    bias = st.bias_paths(steps)
+    inline = st.run(steps, bias, use_res_vec=True, predict="inline")
+    side = st.run(steps, bias, use_res_vec=True, predict="side")
+    off = st.run(steps, bias, use_res_vec=True, predict="off")
+    assert np.array_equal(inline.counts, side.counts) and np.array_equal(inline.counts, off.counts)
+    assert np.array_equal(inline.pred_counts, side.pred_counts)
+    assert not off.acc and set(side.acc) == {1, 4, 8}
