@@ -381,15 +381,27 @@ __global__ __launch_bounds__(64) void fold_residual_kernel(int d, const float *_
     if (lane == 0) bias_out[e] = acc + (bias != nullptr ? bias[e] : 0.f);
 }
 
-__global__ __launch_bounds__(256) void hist_top_kernel(int R, int N, int p, const int32_t *__restrict__ idx,
-                                                       int32_t *__restrict__ pred_counts, int32_t *__restrict__ top)
+// Workload histogram of R predicted selections and its p largest entries.  One block of 16 wavefronts, each with a
+// private LDS histogram (one shared set of 128 bins serialises on the popular experts), summed in wave order.
+#define HT_THREADS 1024
+__global__ __launch_bounds__(HT_THREADS) void hist_top_kernel(int R, int N, int p, const int32_t *__restrict__ idx,
+                                                              int32_t *__restrict__ pred_counts, int32_t *__restrict__ top)
 {
+    __shared__ int sub[HT_THREADS / 64][MOE_MAX_EXPERTS];
     __shared__ int hist[MOE_MAX_EXPERTS];
-    if (threadIdx.x < MOE_MAX_EXPERTS) hist[threadIdx.x] = 0;
+    const int wave = threadIdx.x >> 6;
+    for (int j = threadIdx.x; j < (HT_THREADS / 64) * MOE_MAX_EXPERTS; j += HT_THREADS) (&sub[0][0])[j] = 0;
     __syncthreads();
-    for (int r = threadIdx.x; r < R; r += 256) atomicAdd(&hist[idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
+    for (int r = threadIdx.x; r < R; r += HT_THREADS) atomicAdd(&sub[wave][idx[r] & (MOE_MAX_EXPERTS - 1)], 1);
     __syncthreads();
-    if (threadIdx.x < N) pred_counts[threadIdx.x] = hist[threadIdx.x];
+    if (threadIdx.x < MOE_MAX_EXPERTS) {
+        int c = 0;
+#pragma unroll
+        for (int w = 0; w < HT_THREADS / 64; ++w) c += sub[w][threadIdx.x];
+        hist[threadIdx.x] = c;
+        if ((int)threadIdx.x < N) pred_counts[threadIdx.x] = c;
+    }
+    __syncthreads();
     if (threadIdx.x < 64) top_p_of(hist[threadIdx.x], hist[threadIdx.x + 64], N, p, top, threadIdx.x);
 }
 
@@ -552,7 +564,7 @@ int moe_predict_impl(const moe_shape *s, const void *h, const float *res_vec, co
     float *wl[1] = {route_logits_scratch(s, workspace, 1)};
     int rc = launch_gate_topk(s, h, st, 1, &j, wl);
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(hist_top_kernel, dim3(1), dim3(256), 0, st, (int)R, s->N, p, idx, pred_counts, top_experts);
+    hipLaunchKernelGGL(hist_top_kernel, dim3(1), dim3(HT_THREADS), 0, st, (int)R, s->N, p, idx, pred_counts, top_experts);
     MOE_CHECK_LAUNCH();
     return MOE_OK;
 }

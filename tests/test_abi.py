@@ -100,3 +100,28 @@ def test_entry_points_reject_null_and_misaligned_pointers_before_launching(lib):
     assert lib.moe_pack_weights(8, 500, 256, p, C.c_void_p(0x2000), z) == MOE_EINVAL              # rows not a multiple of 16
     assert lib.moe_pack_weights(8, 512, 250, p, C.c_void_p(0x2000), z) == MOE_EINVAL              # K not a multiple of 32
     assert lib.moe_pack_weights(8, 512, 256, p, p, z) == MOE_EINVAL                               # in place
+
+
+def test_new_entry_points_reject_bad_arguments_before_launching(lib):
+    s = Shape(16, 256, 8, 2, 512, 0)
+    p = C.c_void_p(0x1000)
+    z = C.c_void_p(0)
+    lib.moe_res_vec_workspace_bytes.restype = C.c_size_t
+    assert lib.moe_res_vec_workspace_bytes(256) >= 64 * 256 * 8
+    assert lib.moe_res_vec_workspace_bytes(0) == 0
+    assert lib.moe_res_vec_accumulate(10, 250, p, p, p, p, z) == MOE_EINVAL       # d not a multiple of 8
+    assert lib.moe_res_vec_accumulate(-1, 256, p, p, p, p, z) == MOE_EINVAL
+    assert lib.moe_res_vec_accumulate(10, 256, z, p, p, p, z) == MOE_EINVAL       # no h_cur
+    assert lib.moe_res_vec_accumulate(10, 256, p, p, z, p, z) == MOE_EINVAL       # no accumulator
+    assert lib.moe_res_vec_accumulate(10, 256, p, p, C.c_void_p(0x1004), p, z) == MOE_EINVAL
+    assert lib.moe_res_vec_finish(256, p, C.c_int64(0), p, z) == MOE_EINVAL       # empty calibration set
+    assert lib.moe_res_vec_finish(256, z, C.c_int64(5), p, z) == MOE_EINVAL
+    # moe_route_predict: the union of the two calls' checks, and the workspace is required
+    rp = lambda *a: lib.moe_route_predict(C.byref(s), *a)
+    assert rp(p, p, z, 1, p, p, p, p, p, p, p, p, z, 2, p, p, z, z) == MOE_EINVAL            # no workspace
+    assert rp(p, p, z, 1, p, p, p, p, p, p, z, p, z, 2, p, p, p, z) == MOE_EINVAL            # no res_vec
+    assert rp(p, p, z, 1, p, p, p, p, p, p, p, p, z, 9, p, p, p, z) == MOE_EINVAL            # p > N
+    assert rp(p, p, z, 3, p, p, p, p, p, p, p, p, z, 2, p, p, p, z) == MOE_EINVAL            # bad norm mode
+    assert rp(p, p, z, 1, p, p, p, p, p, p, C.c_void_p(0x1004), p, z, 2, p, p, p, z) == MOE_EINVAL   # res_vec alignment
+    assert rp(p, p, z, 1, p, p, p, p, p, p, p, p, z, 2, p, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
+    assert lib.moe_predict_workload(C.byref(s), p, C.c_void_p(0x1004), p, z, 2, p, p, p, z) == MOE_EINVAL
