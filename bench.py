@@ -29,8 +29,8 @@ PEAK_BF16_MFMA = 2.5e15   # flop/s, MI355X dense bf16 matrix peak
 PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
 # HBM bytes per launch of the dominant kernels (fetched + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this script, scaled by what the same counters read for a plain 1 GiB copy (see profiles/)
-TRAFFIC_PREFILL_UP = 2.61e9 + 87.2e6
-TRAFFIC_DECODE_UP = {1: 470.0e6, 16: 1.176e9 + 0.75e6}
+TRAFFIC_PREFILL_UP = 2.003e9 + 87.3e6
+TRAFFIC_DECODE_UP = {1: 470.0e6, 16: 1.175e9 + 0.75e6}
 
 
 def log(*a):
@@ -203,7 +203,7 @@ def main():
     value = T / (wall / args.steps)
     log(f"[bench] prefill T={T}: {ms_per_step:.3f} ms/step, up {up * 1e3:.3f} ms, ffn {ffn * 1e3:.3f} ms, "
         f"counts={counts.tolist()}, rows_on={rows_on}")
-    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0,4> (gate/up projection + SwiGLU)",
+    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0,4,8> (gate/up projection + SwiGLU)",
                 "achieved": up_flops / up / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                 "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": TRAFFIC_PREFILL_UP,
                 "ffn_achieved": ffn_flops / ffn / 1e12, "ffn_frac": ffn_flops / ffn / PEAK_BF16_MFMA,
