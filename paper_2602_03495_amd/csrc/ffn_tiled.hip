@@ -81,19 +81,22 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     const int NOUT = MODE == 0 ? I : d;
     const int n0 = nt * NT_COLS;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: lets the weight addresses live in SGPRs
     const int li = lane & 15, lg = lane >> 4;
     const int kb_n = K / 32;                               // k32 blocks per weight row block
     const size_t rb_stride = (size_t)kb_n * 512;           // elements between consecutive 16-row blocks
 
     // ---- this wave's weight fragments: consecutive row blocks, so one pointer per matrix + a uniform stride
-    const uint16_t *wp0, *wp1;
+    // (wave-uniform byte base + a 32-bit lane offset: the loads take the scalar-base addressing form)
+    const char *wp0, *wp1;
+    const uint32_t wlane = lane * 16;
     {
         int col = n0 + wave * WAVE_COLS;
         if (col >= NOUT) col = NOUT - WAVE_COLS;           // a wave past the ragged edge recomputes the last columns
-        const size_t mat = (size_t)e * d * I + (size_t)(col >> 4) * rb_stride + lane * 8;
-        wp0 = wa + mat;
-        wp1 = MODE == 0 ? wb + mat : wp0;
+        const size_t mat = (size_t)e * d * I + (size_t)(col >> 4) * rb_stride;
+        wp0 = reinterpret_cast<const char *>(wa + mat);
+        wp1 = MODE == 0 ? reinterpret_cast<const char *>(wb + mat) : wp0;
     }
     // ---- token tile loader: thread -> rows tid/8 + 64 j (j < 2), 16-byte chunk tid%8 of the 128-byte k64 segment
     const int xc = tid & 7;
@@ -103,12 +106,12 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     for (int j = 0; j < XJ; ++j) {
         int r = (tid >> 3) + 64 * j;
         if (r >= nrows) r = nrows - 1;
-        if (MODE == 0)
-            xo[j] = (uint32_t)(perm[row0 + r] / k) * (uint32_t)d + xc * 8;
+        if (MODE == 0)                                      // byte offsets: T*d < 2^31 elements keeps them in 32 bits
+            xo[j] = ((uint32_t)(perm[row0 + r] / k) * (uint32_t)d + xc * 8) * 2u;
         else
-            xo[j] = (uint32_t)r * (uint32_t)I + xc * 8;
+            xo[j] = ((uint32_t)r * (uint32_t)I + xc * 8) * 2u;
     }
-    const uint16_t *xbase = MODE == 0 ? xsrc : xsrc + (size_t)row0 * I;
+    const char *xbase = reinterpret_cast<const char *>(MODE == 0 ? xsrc : xsrc + (size_t)row0 * I);
     uint16_t *xw = &Xs[0][xc >> 2][(tid >> 3) * 32 + (xc & 3) * 8];   // + buffer * 2*TM*32 + j * 64 rows
     const uint16_t *xrd = &Xs[0][0][li * 32 + lg * 8];               // + buffer * 2*TM*32 + half * TM*32 + t * 16 rows
 
@@ -125,21 +128,24 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     u32x4 xg[2][XJ];              // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
     bf16x8 xf[NTT];
 
-#define KSTEP(s) (((s) + 2 * st0) % nk)
-#define KSTAGE(st) (((st) + st0) % nst)
+    // Weight steps and token stages are loaded strictly in ring order, so one running position each replaces a
+    // modulo per load: kw = k32 step of the next weight load, kx = k64 stage of the next token load.
+    int kw = 2 * st0, kx = st0;
 #define WLOAD(set, s)                                                                            \
     do {                                                                                         \
-        const size_t ko_ = (size_t)KSTEP(s) * 512;                                               \
+        const size_t ko_ = (size_t)kw * 1024;                                                    \
+        kw = kw + 1 == nk ? 0 : kw + 1;                                                          \
         _Pragma("unroll") for (int f = 0; f < HF; ++f) {                                         \
-            wr[set][f] = *reinterpret_cast<const u32x4 *>(wp0 + f * rb_stride + ko_);            \
-            if (MODE == 0) wr[set][f + HF] = *reinterpret_cast<const u32x4 *>(wp1 + f * rb_stride + ko_); \
+            wr[set][f] = *reinterpret_cast<const u32x4 *>(wp0 + (f * rb_stride * 2 + ko_) + wlane); \
+            if (MODE == 0) wr[set][f + HF] = *reinterpret_cast<const u32x4 *>(wp1 + (f * rb_stride * 2 + ko_) + wlane); \
         }                                                                                        \
     } while (0)
 #define XLOAD(set, st)                                                                           \
     do {                                                                                         \
-        const size_t ko_ = (size_t)KSTAGE(st) * 64;                                              \
+        const size_t ko_ = (size_t)kx * 128;                                                     \
+        kx = kx + 1 == nst ? 0 : kx + 1;                                                         \
         _Pragma("unroll") for (int j = 0; j < XJ; ++j)                                           \
-            xg[set][j] = *reinterpret_cast<const u32x4 *>(xbase + xo[j] + ko_);                  \
+            xg[set][j] = *reinterpret_cast<const u32x4 *>(xbase + ko_ + xo[j]);                  \
     } while (0)
 #define XSTORE(buf)                                                                              \
     do {                                                                                         \
@@ -188,8 +194,6 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #undef XSTORE
 #undef XLOAD
 #undef WLOAD
-#undef KSTAGE
-#undef KSTEP
 
     // ---- epilogue: in every 16x16 tile a lane holds weight rows 4*lg + 0..3 (= output columns) of token li
     const int colw = n0 + wave * WAVE_COLS;
