@@ -49,7 +49,7 @@ extern "C" {
 /* which expert-FFN kernels to use */
 #define MOE_FFN_AUTO   0      /* skinny when T <= 16, tiled otherwise */
 #define MOE_FFN_TILED  1      /* LDS-tiled bf16 MFMA grouped GEMMs (prefill) */
-#define MOE_FFN_SKINNY 2      /* weight-streaming path for at most 16 rows per expert (decode); needs T <= 16 */
+#define MOE_FFN_SKINNY 2      /* weight-streaming path for at most 16 rows per expert (decode); needs T <= 16, d <= 4096 */
 
 typedef struct moe_shape {
     int32_t T;         /* tokens in the batch */

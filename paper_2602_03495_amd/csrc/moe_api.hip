@@ -100,7 +100,9 @@ int moe_expert_ffn_stage(const moe_shape *s, const void *h, const int32_t *perm,
     if (!aligned16(h) || !aligned16(w1) || !aligned16(w3) || !aligned16(w2) || !aligned16(y)) return MOE_EINVAL;
     if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
     int path = s->ffn_path;
-    if (path == MOE_FFN_AUTO) path = s->T <= MOE_SKINNY_MAX_T ? MOE_FFN_SKINNY : MOE_FFN_TILED;
+    // the decode path keeps a wave's share of the hidden dimension in registers: at most 4096 wide
+    if (path == MOE_FFN_AUTO)
+        path = s->T <= MOE_SKINNY_MAX_T && s->d <= MOE_SKINNY_WAVES * MOE_SKINNY_MAX_STEPS * 32 ? MOE_FFN_SKINNY : MOE_FFN_TILED;
     if (path == MOE_FFN_SKINNY)
         return moe_ffn_skinny_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, stages, (hipStream_t)stream);
     if (path == MOE_FFN_TILED)

@@ -325,3 +325,13 @@ def test_route_predict_equals_the_two_calls(gpu, name, T):
         assert torch.equal(getattr(ra, f), getattr(rb, f)), f
     assert torch.equal(pca, pcb) and torch.equal(topa, topb)
     assert int(pcb.sum()) == T * cfg.k and int(rb.counts.sum()) == T * cfg.k
+
+
+@pytest.mark.parametrize("T", [16, 40])
+def test_largest_hidden_size_and_expert_count(gpu, T):
+    # the limits of the interface at once: d = 8192, N = 128 experts, k = 8 (the decode kernels stop at d = 4096,
+    # so the automatic path choice has to take the tiled kernels for the 16-token batch as well)
+    B, Lm = gpu
+    cfg = wl.scaled(wl.CONFIGS["qwen3"], d=8192, I=128)
+    print(f"limits d=8192 N=128 k=8 T={T}", flush=True)
+    _run_layer(B, Lm, cfg, T, [wl.mask_random(cfg, 96)], B.FFN_AUTO)
