@@ -47,7 +47,7 @@ extern "C" {
 #define MOE_NORM_RENORM 1     /* the k selected scores divided by their sum (= softmax over the k logits) */
 
 /* which expert-FFN kernels to use */
-#define MOE_FFN_AUTO   0      /* skinny when T <= 16, tiled otherwise */
+#define MOE_FFN_AUTO   0      /* skinny when T <= 16 and d <= 4096, tiled otherwise */
 #define MOE_FFN_TILED  1      /* LDS-tiled bf16 MFMA grouped GEMMs (prefill) */
 #define MOE_FFN_SKINNY 2      /* weight-streaming path for at most 16 rows per expert (decode); needs T <= 16, d <= 4096 */
 
