@@ -4,12 +4,17 @@
 //   gate_topk_kernel      16 tokens per block; logits by bf16 MFMA 16x16x32 straight from global memory
 //                         (K split over the 8 waves, reduced through LDS), then softmax and top-k per token
 //                         inside one wavefront: k rounds of a DPP max reduction + ballot.
-//   hist_scan_perm_kernel one block per expert: LDS-staged histogram of all selections (LDS atomics),
-//                         exclusive scan, and a ballot-based stable compaction of that expert's rows.
+//   hist_scan_perm_kernel one block per expert: register counts of the selections below / equal to the expert
+//                         (= its offset and workload), then a ballot-based stable compaction of its rows.
+//   Decode-sized batches (T <= 16, T*k <= 128) need no second kernel: the selecting block builds a 16-bit
+//   token mask per expert in LDS, and workload, scan and permutation are popcounts of it.  With more than 16
+//   experts the gate product of such a batch is first spread over one block per 16 experts.
 // moe_predict_workload (Section "Residual-Based Prefetching"):
-//   fold_residual_kernel  bias'[e] = bias[e] + res_vec . W[e]   so that  (h + res_vec) . W + bias = h . W + bias'
-//   gate_topk_kernel      on the next layer's gate with bias'
-//   hist_top_kernel       histogram of the predicted experts and the p largest workloads.
+//   the same kernels on the next layer's gate with bias'[e] = bias[e] + res_vec . W[e], so that
+//   (h + res_vec) . W + bias = h . W + bias'.  Decode-sized: the fold happens inside the gate kernel and the
+//   selecting block emits the workloads and their p largest.  Larger: fold_residual_kernel, gate_topk_kernel,
+//   hist_top_kernel.
+// moe_route_predict: both gates as two "jobs" of the same launches (blockIdx.z) at decode sizes.
 #include "moe_common.h"
 
 #define ROUTE_TOKENS 16      // tokens per block of gate_topk_kernel
