@@ -28,20 +28,17 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(b
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// float -> bf16 bits, round to nearest even (NaN kept quiet)
-__device__ __forceinline__ uint32_t f32_to_bf16(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u)
-        return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// float -> bf16, round to nearest even, by the hardware conversion of gfx950 (v_cvt_pk_bf16_f32: two values per
+// instruction, NaN stays NaN)
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16x2(f, 0.f) & 0xffffu; }
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -82,7 +79,8 @@ __device__ __forceinline__ float wave_sum_dpp(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+// silu(g) * u with the hardware reciprocal (1 ulp) in place of an IEEE division: the result is rounded to bf16 anyway
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
 
 // ---- work items of the experts that have rows and are masked on, without a schedule pass --------------------
 // A launch of (upper bound of working experts) x per_expert blocks: every wave derives the working set itself
