@@ -157,10 +157,11 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                          \
             xf[t] = as_frag(*reinterpret_cast<const u32x4 *>(xrd + (buf) * (2 * TM * 32) + (half) * (TM * 32) + t * (16 * 32))); \
     } while (0)
+    /* token subtile outermost: the first NF MFMAs need only the first LDS read, so the later reads land behind them */ \
 #define MFMAS(set)                                                                               \
     do {                                                                                         \
-        _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
-            _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                      \
+        _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                          \
+            _Pragma("unroll") for (int f = 0; f < NF; ++f)                                       \
                 acc[f][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(wr[set][f]), xf[t], acc[f][t], 0, 0, 0); \
     } while (0)
     // stage st: k32 steps 2 st (weight set ws_) and 2 st + 1; X(st) is in LDS buffer st % 2
