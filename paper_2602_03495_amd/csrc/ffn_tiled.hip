@@ -68,7 +68,7 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
 // Weight tile of a block: 8 waves x NF fragments x 16 rows.  NTT = 16-row token subtiles computed (rows past
 // nrows are clamped copies whose results are dropped).
-template <int MODE, int NF, int NTT>
+template <int MODE, int NF, int NTT, int NSETS>
 __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int I, int k, const uint16_t *__restrict__ xsrc,
                                           const int32_t *__restrict__ perm, const uint16_t *__restrict__ wa,
                                           const uint16_t *__restrict__ wb, uint16_t *__restrict__ out, int e, int nt,
@@ -121,10 +121,11 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #pragma unroll
         for (int t = 0; t < NTT; ++t) acc[f][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = kb_n;          // k32 steps (a multiple of 4: K % 128 == 0)
+    const int nk = kb_n;          // k32 steps (a multiple of NSETS: the launch checks K)
     const int nst = nk / 2;       // k64 stages
     const int st0 = (int)(((unsigned)e * 5u) % (unsigned)nst);   // where this item's K ring starts (per expert: tiles that share rows or weights stay in step)
-    u32x4 wr[4][NF];              // W(step) lives in set step % 4, loaded 3 steps ahead
+    static_assert(NSETS == 4 || NSETS == 8, "an even number of stages per unrolled round");
+    u32x4 wr[NSETS][NF];          // W(step) lives in set step % NSETS, loaded NSETS - 1 steps ahead
     u32x4 xg[2][XJ];              // X(stage) lives in set stage % 2: loaded 2 stages ahead, stored to LDS 1 stage ahead
     bf16x8 xf[NTT];
 
@@ -164,30 +165,30 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
             _Pragma("unroll") for (int f = 0; f < NF; ++f)                                       \
                 acc[f][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(wr[set][f]), xf[t], acc[f][t], 0, 0, 0); \
     } while (0)
-    // stage st: k32 steps 2 st (weight set ws_) and 2 st + 1; X(st) is in LDS buffer st % 2
-#define STAGE(buf, ws_, st)                                                                      \
+    // one stage: k32 steps in weight sets ws_ and ws_ + 1; its token rows are in LDS buffer buf
+#define STAGE(buf, ws_)                                                                          \
     do {                                                                                         \
-        __builtin_amdgcn_s_waitcnt(0xC07F);      /* lgkmcnt(0): this thread's LDS writes of X(st) have landed */ \
+        __builtin_amdgcn_s_waitcnt(0xC07F);      /* lgkmcnt(0): this thread's LDS writes of the stage have landed */ \
         __builtin_amdgcn_s_barrier();                                                            \
-        XLOAD(buf, (st) + 2);                     /* register set st%2 held X(st), which is in LDS now */         \
-        WLOAD(((ws_) + 3) & 3, 2 * (st) + 3);                                                    \
+        XLOAD(buf, 0);                            /* two stages ahead; its register set is in LDS now */          \
+        WLOAD(((ws_) + NSETS - 1) % NSETS, 0);                                                   \
         XREAD(buf, 0);                                                                           \
         MFMAS(ws_);                                                                              \
-        WLOAD(((ws_) + 4) & 3, 2 * (st) + 4);                                                    \
+        WLOAD(ws_, 0);                            /* = set (ws_ + NSETS) % NSETS */              \
         XREAD(buf, 1);                                                                           \
-        MFMAS(((ws_) + 1) & 3);                                                                  \
-        XSTORE((buf) ^ 1);                        /* X(st+1) -> the other LDS buffer */          \
+        MFMAS(((ws_) + 1) % NSETS);                                                              \
+        XSTORE((buf) ^ 1);                        /* the next stage -> the other LDS buffer */   \
     } while (0)
 
     XLOAD(0, 0);
     XLOAD(1, 1);
-    WLOAD(0, 0);
-    WLOAD(1, 1);
-    WLOAD(2, 2);
+#pragma unroll
+    for (int u = 0; u < NSETS - 1; ++u) WLOAD(u, u);
     XSTORE(0);
-    for (int st = 0; st < nst; st += 2) {
-        STAGE(0, 0, st);
-        STAGE(1, 2, st + 1);
+    // a round of NSETS steps (NSETS / 2 stages, an even number, so the LDS buffer of a stage is a constant too)
+    for (int s = 0; s < nk; s += NSETS) {
+#pragma unroll
+        for (int u = 0; u < NSETS; u += 2) STAGE((u >> 1) & 1, u);
     }
 #undef STAGE
 #undef MFMAS
@@ -222,7 +223,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 
 // NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
 // body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
-template <int MODE, int NF, int NTT_MAX, bool DIRECT, bool DYN>
+template <int MODE, int NF, int NTT_MAX, bool DIRECT, bool DYN, int NSETS>
 __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, int N, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;
     nrows = nrows > TM ? TM : nrows;
-#define BODY(n) tile_body<MODE, NF, n>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows)
+#define BODY(n) tile_body<MODE, NF, n, NSETS>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows)
     if (!DYN) BODY(NTT_MAX);
     else if (NTT_MAX == 1 || nrows <= 16) BODY(1);
     else if (NTT_MAX == 2 || nrows <= 32) BODY(2);
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
 #undef BODY
 }
 
-template <int MODE, int NF, int NTT, bool DIRECT>
+template <int MODE, int NF, int NTT, bool DIRECT, int NSETS>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
                          const uint8_t *mask, uint16_t *out, hipStream_t st)
@@ -276,29 +277,46 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
     // a block sizes its body to its own rows when tiles are sparsely filled on average (under 128 rows per expert);
     // with fuller tiles the single full-size body is the faster code
-    if ((long)s->T * s->k >= (long)TM * s->N)
-        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, false>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, s->N, x, perm,
-                           offsets, counts, wa, wb, sched, mask, out);
-    else
-        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, true>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k, s->N, x, perm,
-                           offsets, counts, wa, wb, sched, mask, out);
+    bool full_tiles = false;
+    if constexpr (!DIRECT) full_tiles = (long)s->T * s->k >= (long)TM * s->N;
+    if (full_tiles) {
+        if constexpr (!DIRECT)
+            hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, false, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I,
+                               s->k, s->N, x, perm, offsets, counts, wa, wb, sched, mask, out);
+    } else {
+        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, true, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
+                           s->N, x, perm, offsets, counts, wa, wb, sched, mask, out);
+    }
 }
 
-// Weight fragments per wave (NF) and 16-row token subtiles per tile (NTT).  An expert never receives more rows
-// than there are tokens, so T bounds the subtiles in use, and up to 128 tokens every expert has at most one token
-// tile, which needs no schedule; narrow weight tiles keep every compute unit busy when there are few token tiles.
+// Weight fragments per wave (NF), 16-row token subtiles per tile (NTT) and weight register sets (NSETS).  An expert
+// never receives more rows than there are tokens, so T bounds the subtiles in use, and up to 128 tokens every expert
+// has at most one token tile, which needs no schedule; narrow weight tiles keep every compute unit busy when there
+// are few token tiles, and since a narrow tile leaves a wave only NF KB per step to ask for, it prefetches further
+// ahead (8 register sets, K permitting; 16 measured no better: the token loads, two stages ahead, sit between the
+// weight loads in the in-order vmcnt queue and bound the useful depth).
 template <int MODE>
 static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16_t *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *counts, const uint16_t *wa, const uint16_t *wb,
                            const int32_t *sched, const uint8_t *mask, uint16_t *out, hipStream_t st)
 {
-#define GO(NF_, NTT_, D_) launch_tiled<MODE, NF_, NTT_, D_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, st)
-#define GO3(NTT_, D_)                                      \
-    do {                                                   \
-        if constexpr (MODE == 1) {                         \
-            if (nf == 1) { GO(1, NTT_, D_); break; }       \
-        }                                                  \
-        if (nf == 2) GO(2, NTT_, D_); else GO(4, NTT_, D_);\
+    const int K = MODE == 0 ? s->d : s->I;
+#define GO(NF_, NTT_, D_, NS_) launch_tiled<MODE, NF_, NTT_, D_, NS_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, st)
+#define GO3(NTT_, D_)                                                          \
+    do {                                                                       \
+        if constexpr (MODE == 1) {                                             \
+            if (nf == 1) {                                                     \
+                if (K % 256 == 0) GO(1, NTT_, D_, 8);                          \
+                else GO(1, NTT_, D_, 4);                                       \
+                break;                                                         \
+            }                                                                  \
+            if (nf == 2) {                                                     \
+                if (K % 256 == 0) GO(2, NTT_, D_, 8);                          \
+                else GO(2, NTT_, D_, 4);                                       \
+                break;                                                         \
+            }                                                                  \
+        }                                                                      \
+        GO(4, NTT_, D_, 4);                                                    \
     } while (0)
     if (s->T <= 16) GO3(1, true);
     else if (s->T <= 32) GO3(2, true);
