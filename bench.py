@@ -91,6 +91,89 @@ def time_graph_replays(torch, L, hd, dw, mask_d, steps, warmup):
     return time.perf_counter() - t0
 
 
+def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
+    """One JSON-able record per batch size: the whole step (route, masked routed FFN, shared experts, combine) with HIP
+    events between the calls, and the FFN's share of the bf16 MFMA / HBM peaks."""
+    cfg = wl.CONFIGS[name]
+    w1, w3, w2 = wl.expert_weights(cfg)
+    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2, wl.shared_expert_weights(cfg))
+    out = []
+    for T in Ts:
+        L = Lm.MoeLayer(cfg, T)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
+        L.route(hd, dw)
+        torch.cuda.synchronize()
+        counts = L.routing.counts.cpu().numpy()
+        mask = {"all": np.ones(cfg.N, np.uint8), "half": wl.mask_top_by_counts(counts, cfg.N // 2),
+                "rand6": wl.mask_random(cfg, 6)}[mask_kind]
+        md, on = torch.from_numpy(mask).cuda(), mask.astype(bool)
+
+        def step(ev=None):
+            L.route(hd, dw)
+            if ev: ev[0].record()
+            L.expert_ffn(hd, dw, md)
+            if ev: ev[1].record()
+            if cfg.n_shared: L.shared_ffn(hd, dw)
+            if ev: ev[2].record()
+            L.combine(md)
+            if ev: ev[3].record()
+        for _ in range(3):
+            step()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(evs[i])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        ffn = sum(e[0].elapsed_time(e[1]) for e in evs) / steps * 1e-3
+        sh = sum(e[1].elapsed_time(e[2]) for e in evs) / steps * 1e-3
+        rows_on, active = int(counts[on].sum()), int(((counts > 0) & on).sum())
+        rec = {"workload": name, "tokens": T, "mask": mask_kind, "us_per_step": wall * 1e6, "tokens_per_s": T / wall,
+               "ffn_us": ffn * 1e6, "ffn_mfma_frac": 6.0 * cfg.d * cfg.I * rows_on / ffn / PEAK_BF16_MFMA,
+               "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * active / ffn / PEAK_HBM, "shared_us": sh * 1e6 if cfg.n_shared else 0.0,
+               "active_experts": active, "rows_on": rows_on}
+        log(f"[bench] {name:9s} T={T:5d} step {wall * 1e6:8.1f} us | ffn {ffn * 1e6:8.1f} us mfma {rec['ffn_mfma_frac']:.3f} "
+            f"hbm {rec['ffn_hbm_frac']:.3f} | shared {rec['shared_us']:7.1f} us | active {active} rows_on {rows_on}")
+        out.append(rec)
+    del dw
+    torch.cuda.empty_cache()
+    return out
+
+
+def survey_mid(torch, B, Lm, wl, name, Ts=(32, 64, 128, 256, 512, 1024), steps=20):
+    """Mid-sized batches, no mask: up and down projection separately, as fractions of the HBM peak of the touched
+    experts' weights (median of HIP-event timings)."""
+    cfg = wl.CONFIGS[name]
+    w1, w3, w2 = wl.expert_weights(cfg)
+    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2)
+    out = []
+    for T in Ts:
+        L = Lm.MoeLayer(cfg, T)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
+        L.route(hd, dw)
+        torch.cuda.synchronize()
+        r = L.routing
+        active = int((r.counts > 0).sum())
+        rec = {"workload": name, "tokens": T, "active_experts": active}
+        for stage, sn, per in ((B.STAGE_UP, "up", 4.0), (B.STAGE_DOWN, "down", 2.0)):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for i in range(steps + 3):
+                if i >= 3: evs[i - 3][0].record()
+                B.moe_expert_ffn_stage(L.shape, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, None, L.y, L.ws, stage)
+                if i >= 3: evs[i - 3][1].record()
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(b) for a, b in evs)[steps // 2] * 1e-3
+            rec[sn + "_us"] = t * 1e6
+            rec[sn + "_hbm_frac"] = per * cfg.d * cfg.I * active / t / PEAK_HBM
+        log(f"[bench] {name:9s} T={T:5d} active {active:3d} | up {rec['up_us']:7.1f} us {rec['up_hbm_frac']:.3f} | "
+            f"down {rec['down_us']:7.1f} us {rec['down_hbm_frac']:.3f}")
+        out.append(rec)
+    del dw
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +185,9 @@ def main():
     ap.add_argument("--stack", action="store_true",
                     help="run the Qwen3-30B-A3B-shaped decode stack instead (48 layers, 256 steps, batch 16, AR(1) routing) "
                          "and print its own JSON line: per-step workload histograms, prediction accuracy, tokens/s")
+    ap.add_argument("--survey", action="store_true",
+                    help="time the other layer shapes instead (DeepSeek-V2-Lite, Qwen1.5-MoE, Qwen3-30B-A3B and Mixtral; prefill, "
+                         "decode and the mid-sized batches between them) and print one JSON line with all records")
     ap.add_argument("--stack-layers", type=int, default=48)
     ap.add_argument("--stack-steps", type=int, default=256)
     ap.add_argument("--calib-copy", action="store_true",
@@ -127,6 +213,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log("[bench] calibration copy done: 5 x (1 GiB read + 1 GiB written)")
+        return
+
+    if args.survey:
+        recs = []
+        for name, Ts, mk in (("mixtral", [2048, 16, 1], "rand6"), ("deepseek", [2048, 16], "half"), ("qwen15", [4096, 1], "all"),
+                             ("qwen3", [2048, 16], "half")):
+            recs += survey_config(torch, B, Lm, wl, name, Ts, mk)
+        mid = []
+        for name in ("mixtral", "deepseek", "qwen3"):
+            mid += survey_mid(torch, B, Lm, wl, name)
+        print(json.dumps({"metric": "MoE-layer step time by shape", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "all layer shapes: prefill, decode and mid-sized batches"},
+                          "steps": recs, "mid_sized": mid}), flush=True)
         return
 
     if args.stack:
