@@ -174,6 +174,42 @@ def survey_mid(torch, B, Lm, wl, name, Ts=(32, 64, 128, 256, 512, 1024), steps=2
     return out
 
 
+def survey_rows_per_expert(torch, B, Lm, wl, steps=20):
+    """The Mixtral-shaped prefill batch under three routings that differ only in rows per expert (the gate bias is the
+    workload's Zipf bias, zero, or +-20 so that two experts take every token): MFMA fraction of either projection."""
+    cfg, T = wl.CONFIGS["mixtral"], 2048
+    w1, w3, w2 = wl.expert_weights(cfg)
+    out = []
+    for kind in ("zipf", "uniform", "two experts"):
+        bias = wl.gate_bias(cfg) if kind == "zipf" else np.zeros(cfg.N, np.float32)
+        if kind == "two experts":
+            bias = np.array([20, 20] + [-20] * (cfg.N - 2), np.float32)
+        dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), bias, w1, w3, w2)
+        L = Lm.MoeLayer(cfg, T)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, T))
+        L.route(hd, dw)
+        torch.cuda.synchronize()
+        r = L.routing
+        c = r.counts.cpu().numpy()
+        rec = {"routing": kind, "counts": c.tolist()}
+        for stage, sn, per in ((B.STAGE_UP, "up", 4.0), (B.STAGE_DOWN, "down", 2.0)):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for i in range(steps + 3):
+                if i >= 3: evs[i - 3][0].record()
+                B.moe_expert_ffn_stage(L.shape, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, None, L.y, L.ws, stage)
+                if i >= 3: evs[i - 3][1].record()
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(b) for a, b in evs)[steps // 2] * 1e-3
+            rec[sn + "_us"] = t * 1e6
+            rec[sn + "_mfma_frac"] = per * cfg.d * cfg.I * float(c.sum()) / t / PEAK_BF16_MFMA
+        log(f"[bench] mixtral T=2048 {kind:11s} counts={c.tolist()} | up {rec['up_us']:7.1f} us mfma {rec['up_mfma_frac']:.3f} | "
+            f"down {rec['down_us']:7.1f} us mfma {rec['down_mfma_frac']:.3f}")
+        out.append(rec)
+        del dw
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -225,7 +261,7 @@ def main():
             mid += survey_mid(torch, B, Lm, wl, name)
         print(json.dumps({"metric": "MoE-layer step time by shape", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": "all layer shapes: prefill, decode and mid-sized batches"},
-                          "steps": recs, "mid_sized": mid}), flush=True)
+                          "steps": recs, "mid_sized": mid, "rows_per_expert": survey_rows_per_expert(torch, B, Lm, wl)}), flush=True)
         return
 
     if args.stack:
