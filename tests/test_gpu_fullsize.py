@@ -59,8 +59,8 @@ def config_mask(cfg, hl):
     return np.ones(cfg.N, np.uint8)                 # qwen15: all experts on
 
 
-CASES = [("mixtral", 2048), ("mixtral", 1), ("mixtral", 16), ("deepseek", 2048), ("deepseek", 16),
-         ("qwen15", 4096), ("qwen15", 1), ("qwen3", 16), ("qwen3", 2048)]
+CASES = [("mixtral", 2048), ("mixtral", 1), ("mixtral", 16), ("mixtral", 64), ("mixtral", 256),   # 64, 256: mid-sized batches
+         ("deepseek", 2048), ("deepseek", 16), ("qwen15", 4096), ("qwen15", 1), ("qwen3", 16), ("qwen3", 128), ("qwen3", 2048)]
 
 
 @pytest.mark.parametrize("name,T", CASES)
