@@ -301,17 +301,18 @@ static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16
                            const int32_t *sched, const uint8_t *mask, uint16_t *out, hipStream_t st)
 {
     const int K = MODE == 0 ? s->d : s->I;
+    const bool deep = K % 256 == 0 && K >= 2048;          // a short K does not pay for the longer prologue
 #define GO(NF_, NTT_, D_, NS_) launch_tiled<MODE, NF_, NTT_, D_, NS_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, st)
 #define GO3(NTT_, D_)                                                          \
     do {                                                                       \
         if constexpr (MODE == 1) {                                             \
             if (nf == 1) {                                                     \
-                if (K % 256 == 0) GO(1, NTT_, D_, 8);                          \
+                if (deep) GO(1, NTT_, D_, 8);                                  \
                 else GO(1, NTT_, D_, 4);                                       \
                 break;                                                         \
             }                                                                  \
             if (nf == 2) {                                                     \
-                if (K % 256 == 0) GO(2, NTT_, D_, 8);                          \
+                if (deep) GO(2, NTT_, D_, 8);                                  \
                 else GO(2, NTT_, D_, 4);                                       \
                 break;                                                         \
             }                                                                  \

@@ -65,6 +65,95 @@ __device__ __forceinline__ void top_p_of(int c0, int c1, int N, int p, int32_t *
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Softmax + top-k of one token inside a wavefront: lane l holds the logits v0 of expert l and v1 of expert l + 64
+// (-inf where there is no expert).  k rounds of: wave-wide max on the DPP crossbar, then the lowest expert index
+// holding that value (ballot + find-first-set; the lower 64 experts are asked first), which is the tie rule "equal
+// scores by ascending index".  Lane s < k returns the s-th selection and its softmax score; sel = sum of the k scores.
+__device__ __forceinline__ void select_token(float v0, float v1, int N, int k, int lane, int &my_idx, float &my_p, float &sel)
+{
+    const float NEG = -__builtin_huge_valf();
+    const float m = wave_max_dpp(fmaxf(v0, v1));
+    const float p0 = v0 > NEG ? expf(v0 - m) : 0.f;
+    const float p1 = v1 > NEG ? expf(v1 - m) : 0.f;
+    const float den = wave_sum_dpp(p0 + p1);
+    my_idx = 0;
+    my_p = 0.f;
+    sel = 0.f;
+    float best = m;
+    for (int s = 0; s < k; ++s) {
+        if (s > 0) best = wave_max_dpp(fmaxf(v0, v1));
+        const unsigned long long b0 = __ballot(v0 == best);
+        const unsigned long long b1 = __ballot(v1 == best);
+        int bi;
+        if (b0 != 0ull) {
+            bi = __ffsll((long long)b0) - 1;
+            if (lane == bi) v0 = NEG;
+        } else if (b1 != 0ull) {
+            bi = __ffsll((long long)b1) - 1 + 64;
+            if (lane + 64 == bi) v1 = NEG;
+        } else {
+            bi = N - 1;                                  // only reachable with NaN logits: stay in range
+        }
+        const float pb = expf(best - m) / den;           // uniform
+        sel += pb;
+        if (lane == s) { my_idx = bi; my_p = pb; }
+    }
+}
+
+// Histogram, scan and stable permutation of a decode-sized batch (T <= 16, R = T*k <= 128 selections in sel_idx, LDS)
+// by one block.  A token selects an expert at most once, so the rows of expert e are one per selecting token, in
+// token order: a 16-bit token mask per expert gives the workload (its popcount) and the rank of a row within its
+// expert (the popcount below the token's bit) without any serial pass.  With perm == nullptr (a prediction) the
+// workloads and the p largest of them are written instead.  Every thread of the block must call it.
+__device__ __forceinline__ void decode_tables(const int *sel_idx, unsigned *tokmask, int *off_s, int T, int N, int k,
+                                              int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+                                              int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
+                                              int32_t *__restrict__ top, int p)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int R = T * k;
+    if (threadIdx.x < MOE_MAX_EXPERTS) tokmask[threadIdx.x] = 0u;
+    __syncthreads();
+    int my_e = -1, my_t = 0;
+    if ((int)threadIdx.x < R) {
+        my_e = sel_idx[threadIdx.x];
+        my_t = threadIdx.x / k;
+        atomicOr(&tokmask[my_e], 1u << my_t);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // workloads of experts lane and lane + 64, and their exclusive prefix sums over all 128 slots
+        const int c0 = lane < N ? __popc(tokmask[lane]) : 0;
+        const int c1 = lane + 64 < N ? __popc(tokmask[lane + 64]) : 0;
+        int s0 = c0, s1 = c1;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u0 = __shfl_up(s0, o, MOE_WAVE), u1 = __shfl_up(s1, o, MOE_WAVE);
+            if (lane >= o) { s0 += u0; s1 += u1; }
+        }
+        const int tot0 = __shfl(s0, 63, MOE_WAVE);
+        if (lane < N) counts[lane] = c0;
+        if (lane + 64 < N) counts[lane + 64] = c1;
+        if (perm == nullptr) {
+            // prediction: the workloads and the p largest of them (equal workloads by ascending index)
+            top_p_of(c0, c1, N, p, top, lane);
+        } else {
+            off_s[lane] = s0 - c0;
+            off_s[lane + 64] = tot0 + s1 - c1;
+            if (lane < N) offsets[lane] = s0 - c0;
+            if (lane + 64 < N) offsets[lane + 64] = tot0 + s1 - c1;
+            if (lane == 0) offsets[N] = R;
+        }
+    }
+    if (perm == nullptr) return;
+    __syncthreads();
+    if ((int)threadIdx.x < R) {
+        const int pos = off_s[my_e] + __popc(tokmask[my_e] & ((1u << my_t) - 1u));
+        perm[pos] = threadIdx.x;
+        inv_perm[threadIdx.x] = pos;
+    }
+}
+
 // One gate to evaluate: the layer's own (routing) or the next layer's (prediction).  A launch carries two jobs and
 // blockIdx.z picks one, so that a decode step can route and predict in the same pair of launches.
 struct gate_job {
@@ -202,34 +291,11 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, 
         const int t = t0 + tt;
         if (t >= T) break;                                   // uniform per wave
         const float NEG = -__builtin_huge_valf();
-        float v0 = lane < N ? lg[tt][lane] : NEG;
-        float v1 = (NT > 4 && lane + 64 < N) ? lg[tt][lane + 64] : NEG;
-        const float m = wave_max_dpp(fmaxf(v0, v1));
-        const float p0 = lane < N ? expf(v0 - m) : 0.f;
-        const float p1 = (NT > 4 && lane + 64 < N) ? expf(v1 - m) : 0.f;
-        const float den = wave_sum_dpp(p0 + p1);
-
-        int my_idx = 0;
-        float my_p = 0.f, sel = 0.f;
-        float best = m;
-        for (int s = 0; s < k; ++s) {
-            if (s > 0) best = wave_max_dpp(fmaxf(v0, v1));
-            const unsigned long long b0 = __ballot(v0 == best);
-            const unsigned long long b1 = __ballot(v1 == best);
-            int bi;
-            if (b0 != 0ull) {
-                bi = __ffsll((long long)b0) - 1;
-                if (lane == bi) v0 = NEG;
-            } else if (b1 != 0ull) {
-                bi = __ffsll((long long)b1) - 1 + 64;
-                if (lane + 64 == bi) v1 = NEG;
-            } else {
-                bi = N - 1;                                  // only reachable with NaN logits: stay in range
-            }
-            const float pb = expf(best - m) / den;           // uniform
-            sel += pb;
-            if (lane == s) { my_idx = bi; my_p = pb; }
-        }
+        const float v0 = lane < N ? lg[tt][lane] : NEG;
+        const float v1 = (NT > 4 && lane + 64 < N) ? lg[tt][lane + 64] : NEG;
+        int my_idx;
+        float my_p, sel;
+        select_token(v0, v1, N, k, lane, my_idx, my_p, sel);
         if (lane < k) {
             topk_idx[(size_t)t * k + lane] = my_idx;
             topk_w[(size_t)t * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
@@ -239,53 +305,37 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, 
     if (counts == nullptr) return;
 
     // ---- decode-sized batch (one block, T <= 16): histogram, scan and stable permutation right here ----------
-    // A token selects an expert at most once, so the rows of expert e are one per selecting token, in token order:
-    // a 16-bit token mask per expert gives the workload (its popcount) and the rank of a row within its expert (the
-    // popcount below the token's bit) without any serial pass.
     __shared__ unsigned tokmask[MOE_MAX_EXPERTS];
     __shared__ int off_s[MOE_MAX_EXPERTS];
-    const int *sel_idx = reinterpret_cast<const int *>(&part[0][0][0]);      // the partial-logit scratch is free again
-    const int R = T * k;
-    if (threadIdx.x < MOE_MAX_EXPERTS) tokmask[threadIdx.x] = 0u;
-    __syncthreads();
-    int my_e = -1, my_t = 0;
-    if ((int)threadIdx.x < R) {
-        my_e = sel_idx[threadIdx.x];
-        my_t = threadIdx.x / k;
-        atomicOr(&tokmask[my_e], 1u << my_t);
-    }
-    __syncthreads();
-    if (wave == 0) {
-        // workloads of experts lane and lane + 64, and their exclusive prefix sums over all 128 slots
-        const int c0 = lane < N ? __popc(tokmask[lane]) : 0;
-        const int c1 = lane + 64 < N ? __popc(tokmask[lane + 64]) : 0;
-        int s0 = c0, s1 = c1;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int u0 = __shfl_up(s0, o, MOE_WAVE), u1 = __shfl_up(s1, o, MOE_WAVE);
-            if (lane >= o) { s0 += u0; s1 += u1; }
-        }
-        const int tot0 = __shfl(s0, 63, MOE_WAVE);
-        if (lane < N) counts[lane] = c0;
-        if (lane + 64 < N) counts[lane + 64] = c1;
-        if (perm == nullptr) {
-            // prediction: the workloads and the p largest of them (equal workloads by ascending index)
-            top_p_of(c0, c1, N, p, top, lane);
-        } else {
-            off_s[lane] = s0 - c0;
-            off_s[lane + 64] = tot0 + s1 - c1;
-            if (lane < N) offsets[lane] = s0 - c0;
-            if (lane + 64 < N) offsets[lane + 64] = tot0 + s1 - c1;
-            if (lane == 0) offsets[N] = R;
+    decode_tables(reinterpret_cast<const int *>(&part[0][0][0]), tokmask, off_s, T, N, k, counts, offsets, perm, inv_perm, top, p);
+}
+
+// Selection for a decode-sized batch from stored logits [T, N] (bias already added): one wavefront per token, then
+// the tables of decode_tables.  One block of 16 waves per job (blockIdx.z).
+#define SELECT_THREADS 1024
+__global__ __launch_bounds__(SELECT_THREADS) void select_decode_kernel(int T, int N, int k, gate_job job0, gate_job job1)
+{
+    const gate_job &J = blockIdx.z == 0 ? job0 : job1;
+    __shared__ int sel_idx[ROUTE_TOKENS * MOE_MAX_TOPK];
+    __shared__ unsigned tokmask[MOE_MAX_EXPERTS];
+    __shared__ int off_s[MOE_MAX_EXPERTS];
+    const int lane = threadIdx.x & 63, t = threadIdx.x >> 6;
+    if (t < T) {
+        const float NEG = -__builtin_huge_valf();
+        const float *row = J.logits_in + (size_t)t * N;
+        const float v0 = lane < N ? row[lane] : NEG;
+        const float v1 = lane + 64 < N ? row[lane + 64] : NEG;
+        int my_idx;
+        float my_p, sel;
+        select_token(v0, v1, N, k, lane, my_idx, my_p, sel);
+        if (lane < k) {
+            J.topk_idx[(size_t)t * k + lane] = my_idx;
+            J.topk_w[(size_t)t * k + lane] = J.norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+            sel_idx[t * k + lane] = my_idx;
         }
     }
-    if (perm == nullptr) return;
     __syncthreads();
-    if ((int)threadIdx.x < R) {
-        const int pos = off_s[my_e] + __popc(tokmask[my_e] & ((1u << my_t) - 1u));
-        perm[pos] = threadIdx.x;
-        inv_perm[threadIdx.x] = pos;
-    }
+    decode_tables(sel_idx, tokmask, off_s, T, N, k, J.counts, J.offsets, J.perm, J.inv_perm, J.top, J.p);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -477,6 +527,10 @@ static int launch_gate_topk(const moe_shape *s, const void *h, hipStream_t st, i
         }
         hipLaunchKernelGGL(gate_topk_kernel<1>, dim3(1, NT, n_jobs), block, 0, st, s->T, s->d, s->N, s->k, hp, lg[0], lg[1]);
         MOE_CHECK_LAUNCH();
+        // T <= 16 and k <= 8: at most 128 selections, so the selecting block also builds the tables
+        hipLaunchKernelGGL(select_decode_kernel, dim3(1, 1, n_jobs), dim3(SELECT_THREADS), 0, st, s->T, s->N, s->k, sel[0], sel[1]);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
     }
 #define GT(n)                                                                                                  \
     case n:                                                                                                    \
