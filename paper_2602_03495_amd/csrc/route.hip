@@ -8,7 +8,8 @@
 //                         (= its offset and workload), then a ballot-based stable compaction of its rows.
 //   Decode-sized batches (T <= 16, T*k <= 128) need no second kernel: the selecting block builds a 16-bit
 //   token mask per expert in LDS, and workload, scan and permutation are popcounts of it.  With more than 16
-//   experts the gate product of such a batch is first spread over one block per 16 experts.
+//   experts the gate product of such a batch is first spread over one block per 16 experts and select_decode_kernel
+//   (one wavefront per token) selects from the stored logits.
 // moe_predict_workload (Section "Residual-Based Prefetching"):
 //   the same kernels on the next layer's gate with bias'[e] = bias[e] + res_vec . W[e], so that
 //   (h + res_vec) . W + bias = h . W + bias'.  Decode-sized: the fold happens inside the gate kernel and the
