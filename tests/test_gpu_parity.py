@@ -335,3 +335,60 @@ def test_largest_hidden_size_and_expert_count(gpu, T):
     cfg = wl.scaled(wl.CONFIGS["qwen3"], d=8192, I=128)
     print(f"limits d=8192 N=128 k=8 T={T}", flush=True)
     _run_layer(B, Lm, cfg, T, [wl.mask_random(cfg, 96)], B.FFN_AUTO)
+
+
+@pytest.mark.parametrize("name", ["mixtral_s", "qwen3_s"])
+def test_graph_replays_equal_eager_runs(gpu, name):
+    # the decode numbers are taken from HIP-graph replays: a captured pass (route + prediction, masked FFN, combine),
+    # replayed several times with new inputs and with eager work and synchronisations in between, must reproduce the
+    # eager results of the same inputs bit for bit
+    B, Lm = gpu
+    cfg = SMALL[name]
+    T, p = 16, min(8, cfg.N)
+    print(f"graph replay {name}", flush=True)
+    hl = make_host_layer(cfg)
+    dw = _upload(Lm, hl)
+    W1, b1 = Lm.to_device_bf16(wl.gate_weights(cfg, 1)), torch.from_numpy(wl.gate_bias(cfg, 1)).cuda()
+    nxt = Lm.LayerWeights(W1, b1, dw.w1, dw.w3, dw.w2)
+    rv = torch.from_numpy(wl.layer_drift(cfg)).cuda()
+    mask = torch.from_numpy(wl.mask_random(cfg, (3 * cfg.N) // 4)).cuda()
+    L = Lm.MoeLayer(cfg, T)
+    top = torch.empty(p, dtype=torch.int32, device="cuda")
+    h_static = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=0)).clone()
+
+    def one_pass():
+        L.route_predict(h_static, dw, rv, nxt, p, top)
+        L.expert_ffn(h_static, dw, mask)
+        L.combine(mask, with_shared=False)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        r = L.routing
+        return [x.clone() for x in (r.topk_idx, r.topk_w, r.counts, r.offsets, r.perm, r.inv_perm, L.pred_counts, top, L.out)]
+
+    inputs = [Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=d_)) for d_ in (1, 2, 3, 1)]
+    eager = []
+    for x in inputs:
+        h_static.copy_(x)
+        one_pass()
+        eager.append(snapshot())
+    assert not torch.equal(eager[0][8], eager[1][8])          # the inputs differ, so do the results
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_pass()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        one_pass()
+    for i, x in enumerate(inputs):
+        h_static.copy_(x)
+        L.out.zero_()                                         # eager work between the replays
+        L.routing.counts.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        got = snapshot()
+        for a, b in zip(got, eager[i]):
+            assert torch.equal(a, b), (i, a.dtype, a.shape)
