@@ -129,7 +129,7 @@ struct moe_ws_layout {
     size_t act;        // [T*k, I] bf16 inner activations
     size_t partial;    // [nsplit, T*k, d] fp32 split-K partial sums of the skinny down projection
     size_t sched;      // tile schedule of the tiled path
-    size_t route;      // routing scratch: folded bias [N], idx [T*k], w [T*k] (prediction), 2 x logits [16, N] (decode-sized gates)
+    size_t route;      // routing scratch: folded bias [N], idx [T*k], w [T*k] (prediction), 2 x logits [max(T,16), N] (gate product and selection in separate launches)
     size_t total;
 };
 
@@ -145,6 +145,13 @@ static inline int moe_skinny_nsplit(int K)
     return (K + per_block - 1) / per_block;
 }
 
+// one [max(T, 16), N] fp32 block of gate logits (the gate product and the selection are separate launches when the
+// gate matrix has many rows)
+static inline size_t moe_logits_scratch_bytes(const moe_shape *s)
+{
+    return moe_align256((size_t)(s->T > 16 ? s->T : 16) * (size_t)s->N * 4);
+}
+
 static inline moe_ws_layout moe_ws(const moe_shape *s)
 {
     moe_ws_layout L;
@@ -158,7 +165,7 @@ static inline moe_ws_layout moe_ws(const moe_shape *s)
     L.sched = off;
     off += moe_align256(((size_t)R / MOE_TILE_M + MOE_MAX_EXPERTS + 8) * 16);
     L.route = off;
-    off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4) + 2 * moe_align256(16 * MOE_MAX_EXPERTS * 4);
+    off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4) + 2 * moe_logits_scratch_bytes(s);
     L.total = off;
     return L;
 }

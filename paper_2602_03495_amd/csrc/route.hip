@@ -218,20 +218,22 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, 
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // K is dealt to the 8 waves in 32-wide steps (step s -> wave s % 8); each wave issues the loads of four of
-    // its steps before the first MFMA so that the block has ~8 x 4 x (1 + NT) loads in flight
+    // its steps before the first MFMA so that the block has ~8 x 4 x (1 + NT) loads in flight (eight at a time
+    // measured no faster)
+    constexpr int BATCH = 4;
     const int nsteps = logits_in != nullptr ? 0 : d >> 5;
     int s = wave;
-    for (; s + 3 * ROUTE_WAVES < nsteps; s += 4 * ROUTE_WAVES) {
-        u32x4 a[4], b[4][NT];
+    for (; s + (BATCH - 1) * ROUTE_WAVES < nsteps; s += BATCH * ROUTE_WAVES) {
+        u32x4 a[BATCH], b[BATCH][NT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             a[u] = *reinterpret_cast<const u32x4 *>(hp + (s + u * ROUTE_WAVES) * 32);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) b[u][nt] = *reinterpret_cast<const u32x4 *>(wp[nt] + (s + u * ROUTE_WAVES) * 32);
         }
         __builtin_amdgcn_sched_barrier(0);      // keep every load of the batch ahead of the first MFMA
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < BATCH; ++u)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
                 acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[u]), as_frag(b[u][nt]), acc[nt], 0, 0, 0);
@@ -337,6 +339,26 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_decode_kernel(int T, in
     }
     __syncthreads();
     decode_tables(sel_idx, tokmask, off_s, T, N, k, J.counts, J.offsets, J.perm, J.inv_perm, J.top, J.p);
+}
+
+// Selection from stored logits [T, N] for any batch size: one wavefront per token, 16 tokens per block.
+__global__ __launch_bounds__(SELECT_THREADS) void select_rows_kernel(int T, int N, int k, gate_job job0, gate_job job1)
+{
+    const gate_job &J = blockIdx.z == 0 ? job0 : job1;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (SELECT_THREADS / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const float NEG = -__builtin_huge_valf();
+    const float *row = J.logits_in + (size_t)t * N;
+    const float v0 = lane < N ? row[lane] : NEG;
+    const float v1 = lane + 64 < N ? row[lane + 64] : NEG;
+    int my_idx;
+    float my_p, sel;
+    select_token(v0, v1, N, k, lane, my_idx, my_p, sel);
+    if (lane < k) {
+        J.topk_idx[(size_t)t * k + lane] = my_idx;
+        J.topk_w[(size_t)t * k + lane] = J.norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -508,7 +530,7 @@ static gate_job make_job(const void *gate_w, const float *bias, int norm_mode, i
 }
 
 // Launches the gate kernels for one job, or for two jobs side by side (decode-sized batches only: both then take the
-// same path).  ws_logits[i]: [16, N] scratch of job i for the split decode path, or null.
+// same path).  ws_logits[i]: [max(T,16), N] scratch of job i for the paths that store logits, or null.
 static int launch_gate_topk(const moe_shape *s, const void *h, hipStream_t st, int n_jobs, gate_job *jobs, float *const *ws_logits)
 {
     const int NT = (s->N + 15) / 16;
@@ -533,6 +555,25 @@ static int launch_gate_topk(const moe_shape *s, const void *h, hipStream_t st, i
         MOE_CHECK_LAUNCH();
         return MOE_OK;
     }
+    if (s->T > ROUTE_TOKENS && NT >= 4 && ws_logits[0] != nullptr) {
+        // many experts: a block that evaluated all of them for its 16 tokens would leave half the chip idle and spend
+        // its time on the gate rows, so the gate product runs as (token blocks x 32-expert slices) and the selection,
+        // one wavefront per token, reads the stored logits
+        gate_job lg[2];
+        for (int i = 0; i < 2; ++i) {
+            const int ji = i < n_jobs ? i : n_jobs - 1;
+            lg[i] = make_job(jobs[ji].gate_w, jobs[ji].bias, jobs[ji].norm_mode, nullptr, nullptr);
+            lg[i].logits_out = ws_logits[ji];
+            sel[i].logits_in = ws_logits[ji];
+        }
+        hipLaunchKernelGGL(gate_topk_kernel<2>, dim3(grid.x, (s->N + 31) / 32, n_jobs), block, 0, st, s->T, s->d, s->N, s->k, hp,
+                           lg[0], lg[1]);
+        MOE_CHECK_LAUNCH();
+        hipLaunchKernelGGL(select_rows_kernel, dim3((s->T + SELECT_THREADS / 64 - 1) / (SELECT_THREADS / 64), 1, n_jobs),
+                           dim3(SELECT_THREADS), 0, st, s->T, s->N, s->k, sel[0], sel[1]);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    }
 #define GT(n)                                                                                                  \
     case n:                                                                                                    \
         hipLaunchKernelGGL(gate_topk_kernel<n>, grid, block, 0, st, s->T, s->d, s->N, s->k, hp, sel[0], sel[1]); \
@@ -553,7 +594,7 @@ static float *route_logits_scratch(const moe_shape *s, void *workspace, int whic
     if (workspace == nullptr) return nullptr;
     moe_ws_layout L = moe_ws(s);
     return (float *)((char *)workspace + L.route + moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256((size_t)s->T * s->k * 4) +
-                     (size_t)which * moe_align256(16 * MOE_MAX_EXPERTS * 4));
+                     (size_t)which * moe_logits_scratch_bytes(s));
 }
 
 static bool single_block_routing(const moe_shape *s) { return s->T <= ROUTE_TOKENS && s->T * s->k <= 128; }
