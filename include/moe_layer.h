@@ -83,8 +83,8 @@ int moe_workspace_bytes(const moe_shape *s, size_t *bytes);
  * h [T,d] bf16 [device]; gate_w [N,d] bf16 [device] (row e = column e of the paper's d x N matrix W_g);
  * gate_bias [N] fp32 [device] or NULL; topk_idx [T,k] int32, topk_w [T,k] fp32, counts [N] int32,
  * offsets [N+1] int32, perm [T*k] int32, inv_perm [T*k] int32: all [device] outputs.
- * workspace [device], 256-byte aligned, >= moe_workspace_bytes() of the same shape, or NULL (then decode-sized
- * batches with more than 16 experts take a slower single-block path).
+ * workspace [device], 256-byte aligned, >= moe_workspace_bytes() of the same shape, or NULL (then gates with many
+ * experts take a slower path that evaluates all experts of 16 tokens in one block; the results are the same).
  */
 int moe_route(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
               int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
