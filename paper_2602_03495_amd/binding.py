@@ -81,7 +81,9 @@ def alloc_workspace(s: MoeShape, device="cuda") -> torch.Tensor:
     return torch.empty(workspace_bytes(s) + 256, dtype=torch.uint8, device=device)
 
 
-def _ws_ptr(ws: torch.Tensor):
+def _ws_ptr(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return C.c_void_p(0)
     p = ws.data_ptr()
     return C.c_void_p((p + 255) & ~255)
 
@@ -103,7 +105,7 @@ def alloc_routing(s: MoeShape, device="cuda") -> Routing:
                    torch.empty(s.N, **i32), torch.empty(s.N + 1, **i32), torch.empty(R, **i32), torch.empty(R, **i32))
 
 
-def moe_route(s: MoeShape, h, gate_w, gate_bias, norm_mode: int, out: Routing, ws: torch.Tensor) -> Routing:
+def moe_route(s: MoeShape, h, gate_w, gate_bias, norm_mode: int, out: Routing, ws: Optional[torch.Tensor]) -> Routing:
     rc = load_library().moe_route(C.byref(s), _ptr(h, torch.bfloat16), _ptr(gate_w, torch.bfloat16),
                                   _ptr(gate_bias, torch.float32), C.c_int(norm_mode), _ptr(out.topk_idx, torch.int32),
                                   _ptr(out.topk_w, torch.float32), _ptr(out.counts, torch.int32),

@@ -392,3 +392,23 @@ def test_graph_replays_equal_eager_runs(gpu, name):
         got = snapshot()
         for a, b in zip(got, eager[i]):
             assert torch.equal(a, b), (i, a.dtype, a.shape)
+
+
+@pytest.mark.parametrize("name,T", [("qwen3_s", 16), ("qwen3_s", 300), ("deepseek_s", 9), ("deepseek_s", 130), ("mixtral_s", 16)])
+def test_route_without_a_workspace_gives_the_same_tables(gpu, name, T):
+    # moe_route may be called with workspace = NULL: gates with many experts then evaluate all experts of 16 tokens in
+    # one block instead of storing logits first; every output must be identical
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"route no-workspace {name} T={T}", flush=True)
+    h = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=5))
+    W, b = Lm.to_device_bf16(wl.gate_weights(cfg)), torch.from_numpy(wl.gate_bias(cfg)).cuda()
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    ra, rb = B.alloc_routing(s), B.alloc_routing(s)
+    B.moe_route(s, h, W, b, cfg.norm_mode, ra, B.alloc_workspace(s))
+    B.moe_route(s, h, W, b, cfg.norm_mode, rb, None)
+    torch.cuda.synchronize()
+    for f in ("topk_idx", "counts", "offsets", "perm", "inv_perm"):
+        assert torch.equal(getattr(ra, f), getattr(rb, f)), f
+    assert torch.allclose(ra.topk_w, rb.topk_w, rtol=1e-6, atol=0)
+    assert int(rb.counts.sum()) == T * cfg.k
