@@ -68,6 +68,25 @@ def time_steps(torch, B, L, hd, dw, mask_d, steps, warmup):
     return wall, up, ffn
 
 
+def median_event_seconds(torch, fn, runs=20, flush=None):
+    """Median over `runs` of the HIP-event time of fn(); flush (a device tensor larger than the 256 MB Infinity Cache) is
+    read through between runs, outside the timed interval, so that a small working set comes from HBM every time (read,
+    not written: dirty lines would have to be written back during the timed call)."""
+    for _ in range(3):
+        fn()
+    ts = []
+    for _ in range(runs):
+        if flush is not None:
+            flush.sum()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        ts.append(a.elapsed_time(b) * 1e-3)
+    return sorted(ts)[runs // 2]
+
+
 def time_graph_replays(torch, L, hd, dw, mask_d, steps, warmup):
     """The same pass captured once in a HIP graph and replayed: removes the host's per-launch cost, which at
     decode sizes is a large share of an eagerly launched step.  Returns wall seconds for `steps` replays."""
@@ -97,7 +116,7 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
     cfg = wl.CONFIGS[name]
     w1, w3, w2 = wl.expert_weights(cfg)
     dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2, wl.shared_expert_weights(cfg))
-    out = []
+    out, flush = [], None
     for T in Ts:
         L = Lm.MoeLayer(cfg, T)
         hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
@@ -129,6 +148,14 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
         ffn = sum(e[0].elapsed_time(e[1]) for e in evs) / steps * 1e-3
         sh = sum(e[1].elapsed_time(e[2]) for e in evs) / steps * 1e-3
         rows_on, active = int(counts[on].sum()), int(((counts > 0) & on).sum())
+        if T <= 16:
+            # a decode step touches few hundred MB at most: flush the Infinity Cache between steps so that it is HBM traffic
+            if flush is None:
+                flush = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB
+            wall = median_event_seconds(torch, step, steps, flush)
+            ffn = median_event_seconds(torch, lambda: L.expert_ffn(hd, dw, md), steps, flush)
+            if cfg.n_shared:
+                sh = median_event_seconds(torch, lambda: L.shared_ffn(hd, dw), steps, flush)
         rec = {"workload": name, "tokens": T, "mask": mask_kind, "us_per_step": wall * 1e6, "tokens_per_s": T / wall,
                "ffn_us": ffn * 1e6, "ffn_mfma_frac": 6.0 * cfg.d * cfg.I * rows_on / ffn / PEAK_BF16_MFMA,
                "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * active / ffn / PEAK_HBM, "shared_us": sh * 1e6 if cfg.n_shared else 0.0,
@@ -136,7 +163,7 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
         log(f"[bench] {name:9s} T={T:5d} step {wall * 1e6:8.1f} us | ffn {ffn * 1e6:8.1f} us mfma {rec['ffn_mfma_frac']:.3f} "
             f"hbm {rec['ffn_hbm_frac']:.3f} | shared {rec['shared_us']:7.1f} us | active {active} rows_on {rows_on}")
         out.append(rec)
-    del dw
+    del dw, flush
     torch.cuda.empty_cache()
     return out
 
@@ -342,7 +369,13 @@ def main():
                 "achieved": up_flops / up / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                 "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": TRAFFIC_PREFILL_UP,
                 "ffn_achieved": ffn_flops / ffn / 1e12, "ffn_frac": ffn_flops / ffn / PEAK_BF16_MFMA,
-                "flops_per_launch": up_flops, "avg_launch_ms": up * 1e3}
+                "flops_per_launch": up_flops, "avg_launch_ms": up * 1e3,
+                # the other bound of the same FFN: weights of the touched masked-on experts once from HBM
+                "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * int(((counts > 0) & on).sum()) / ffn / PEAK_HBM}
+    # the next-layer workload prediction is not part of the step above; alone it costs (next gate = this layer's, a stand-in)
+    rv = torch.from_numpy(wl.layer_drift(cfg)).cuda()
+    top = torch.empty(1, dtype=torch.int32, device="cuda")
+    predict_us = {"prefill_2048": median_event_seconds(torch, lambda: L.predict(hd, rv, dw, 1, top)) * 1e6}
 
     # ---- decode -------------------------------------------------------------------------------------
     decode = []
@@ -364,6 +397,10 @@ def main():
                                         "ffn_frac": ffn_bytes / ffn_d / PEAK_HBM if active else 0.0,
                                         "step_frac": ffn_bytes / (wall_g / args.decode_steps) / PEAK_HBM if active else 0.0,
                                         "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "traffic": TRAFFIC_DECODE_UP.get(Td)}})
+            predict_us[f"decode_{Td}"] = median_event_seconds(torch, lambda: Ld.predict(hdd, rv, dw, 1, top)) * 1e6
+            predict_us[f"decode_{Td}_route_alone"] = median_event_seconds(torch, lambda: Ld.route(hdd, dw)) * 1e6
+            predict_us[f"decode_{Td}_route_and_predict_fused"] = median_event_seconds(
+                torch, lambda: Ld.route_predict(hdd, dw, rv, dw, 1, top)) * 1e6
             log(f"[bench] decode T={Td}: graph {decode[-1]['ms_per_step']:.4f} ms/step, eager {decode[-1]['eager_ms_per_step']:.4f}, "
                 f"up {up_d * 1e3:.4f} ms, ffn {ffn_d * 1e3:.4f} ms, active={active}")
 
@@ -386,7 +423,7 @@ def main():
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "mixtral-8x7b-shaped layer, prefill 2048 tokens", "d": cfg.d, "experts": cfg.N,
                       "top_k": cfg.k, "inner": cfg.I, "experts_on_gpu": int(on.sum()), "tokens": T},
-           "roofline": roofline, "cpu_baseline": cpu, "decode": decode}
+           "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "predict_workload_us": predict_us}
     print(json.dumps(out), flush=True)
 
 
