@@ -280,7 +280,7 @@ def main():
 
     if args.survey:
         recs = []
-        for name, Ts, mk in (("mixtral", [2048, 16, 1], "rand6"), ("deepseek", [2048, 16], "half"), ("qwen15", [4096, 1], "all"),
+        for name, Ts, mk in (("mixtral", [2048, 4096, 8192, 16384, 16, 1], "rand6"), ("deepseek", [2048, 16], "half"), ("qwen15", [4096, 1], "all"),
                              ("qwen3", [2048, 16], "half")):
             recs += survey_config(torch, B, Lm, wl, name, Ts, mk)
         mid = []
