@@ -115,7 +115,7 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
     events between the calls, and the FFN's share of the bf16 MFMA / HBM peaks."""
     cfg = wl.CONFIGS[name]
     w1, w3, w2 = wl.expert_weights(cfg)
-    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2, wl.shared_expert_weights(cfg))
+    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2, wl.shared_expert_weights(cfg), merge_shared=True)
     out, flush = [], None
     for T in Ts:
         L = Lm.MoeLayer(cfg, T)
@@ -160,6 +160,17 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
                "ffn_us": ffn * 1e6, "ffn_mfma_frac": 6.0 * cfg.d * cfg.I * rows_on / ffn / PEAK_BF16_MFMA,
                "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * active / ffn / PEAK_HBM, "shared_us": sh * 1e6 if cfg.n_shared else 0.0,
                "active_experts": active, "rows_on": rows_on}
+        if L.n_merged:
+            # the same layer with its shared experts inside the grouped launches (moe_append_shared)
+            xm = L.merged_mask(md)
+            mstep = lambda: L.forward_merged(hd, dw, xm)
+            for _ in range(3):
+                mstep()
+            wm = median_event_seconds(torch, mstep, steps, flush if T <= 16 else None)
+            ws_ = median_event_seconds(torch, step, steps, flush if T <= 16 else None)
+            rec["merged_us_per_step"], rec["merged_tokens_per_s"], rec["separate_us_per_step"] = wm * 1e6, T / wm, ws_ * 1e6
+            log(f"[bench] {name:9s} T={T:5d} shared experts inside the grouped launches: step {wm * 1e6:8.1f} us "
+                f"(separate launches, timed the same way: {ws_ * 1e6:8.1f} us)")
         log(f"[bench] {name:9s} T={T:5d} step {wall * 1e6:8.1f} us | ffn {ffn * 1e6:8.1f} us mfma {rec['ffn_mfma_frac']:.3f} "
             f"hbm {rec['ffn_hbm_frac']:.3f} | shared {rec['shared_us']:7.1f} us | active {active} rows_on {rows_on}")
         out.append(rec)

@@ -196,6 +196,35 @@ int moe_dense_route(const moe_shape *s, int32_t *counts, int32_t *offsets, int32
 int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *scale, void *stream);
 
 /*
+ * Shared experts inside the grouped launches.  The always-on shared experts of the model table in Section
+ * "Experimental Setup" enter Eq. 2 as further terms of the same sum, so a layer with N routed experts (k per token)
+ * and n_shared shared ones is a layer of N + n_shared experts in which every token takes k + n_shared slots, the last
+ * n_shared of them fixed.  Given the tables moe_route wrote for shape (T, N, k), this call writes the tables of that
+ * wider layer:
+ *
+ *   x_topk_idx[t, s] = topk_idx[t, s] (s < k),  N + (s - k) (s >= k)
+ *   x_topk_w[t, s]   = topk_w[t, s]   (s < k),  c(t)        (s >= k),  c(t) = 1, or 1/(1+exp(-(h[t,:] . w_sg)))
+ *   x_counts[e]      = counts[e] (e < N),  T (e >= N);   x_offsets = their exclusive scan
+ *   x_perm           = the routed rows in their order, then expert N + j's rows t = 0..T-1 (slot ids t*(k+n_shared)+s)
+ *   x_inv_perm       = its inverse
+ *
+ * moe_expert_ffn and moe_combine then run with shape (T, d, N + n_shared, k + n_shared, I), weight arrays holding the
+ * shared experts' matrices after the routed ones, and a mask of N + n_shared entries.  A shared expert whose inner
+ * size is m * I is m shared experts of inner size I with the same weight c(t): its W1 and W3 rows and its W2 columns
+ * split into m consecutive blocks (SwiGLU acts on each inner unit separately, and the down projection sums over them).
+ *
+ * s: the routed shape (s->I unused).  h [T,d] bf16 and w_sg [d] bf16, both 16-byte aligned, or w_sg = NULL for
+ * c(t) = 1 (h is then not read).  Inputs as written by moe_route; outputs x_topk_idx, x_topk_w [T, k+n_shared],
+ * x_counts [N+n_shared], x_offsets [N+n_shared+1], x_perm, x_inv_perm [T*(k+n_shared)]: all [device], none may
+ * alias an input.  Errors: MOE_EINVAL for n_shared < 1, N + n_shared > MOE_MAX_EXPERTS, k + n_shared > MOE_MAX_TOPK,
+ * a NULL table pointer or a misaligned h / w_sg.
+ */
+int moe_append_shared(const moe_shape *s, int n_shared, const void *h, const void *w_sg, const int32_t *topk_idx,
+                      const float *topk_w, const int32_t *counts, const int32_t *offsets, const int32_t *perm,
+                      const int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts, int32_t *x_offsets,
+                      int32_t *x_perm, int32_t *x_inv_perm, void *stream);
+
+/*
  * Calibration of res_vec (Section "Residual-Based Prefetching", the res_vec equation): the mean, over the tokens
  * of a calibration set, of the difference between a token's input feature at the next MoE layer and at this one.
  *

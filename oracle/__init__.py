@@ -164,6 +164,16 @@ def layer(h, topk_idx, topk_w, w1, w3, w2, mask=None, shared=None, shared_mode: 
     return out
 
 
+def shared_scale(h, w_sg) -> np.ndarray:
+    """[T] float64: weight of a sigmoid-gated shared expert, c(t) = 1 / (1 + exp(-(h[t,:] . w_sg))), the shared-expert
+    term of Eq. 2 for the model whose shared expert carries a gate of its own (model table, Section "Experimental
+    Setup").  Plain NumPy in float64 from the bf16-valued inputs."""
+    hb, wb = _u16(h), _u16(w_sg)
+    x = (hb.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    g = (wb.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return 1.0 / (1.0 + np.exp(-(x @ g)))
+
+
 def res_vec(h_cur, h_next) -> np.ndarray:
     """[d] float32: mean over calibration tokens of h_next - h_cur."""
     a, b = _u16(h_cur), _u16(h_next)

@@ -14,11 +14,12 @@ from .build import LIB
 
 FFN_AUTO, FFN_TILED, FFN_SKINNY = 0, 1, 2
 NORM_NONE, NORM_RENORM = 0, 1
+MAX_EXPERTS, MAX_TOPK = 128, 8        # MOE_MAX_EXPERTS, MOE_MAX_TOPK of include/moe_layer.h
 
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
            "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
            "moe_expert_times", "moe_greedy_assign", "moe_cache_step", "moe_res_vec_workspace_bytes",
-           "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict"]
+           "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict", "moe_append_shared"]
 
 
 class MoeShape(C.Structure):
@@ -256,3 +257,15 @@ def moe_shared_gate(s: MoeShape, h, w_sg, scale):
                                         _ptr(scale, torch.float32), _stream())
     _check(rc, "moe_shared_gate")
     return scale
+
+
+def moe_append_shared(s: MoeShape, n_shared: int, h, w_sg, r: Routing, out: Routing) -> Routing:
+    """Tables of the layer with its shared experts appended as experts N.. and slots k.. (out: shapes of N+n_shared, k+n_shared)."""
+    i32 = torch.int32
+    rc = load_library().moe_append_shared(C.byref(s), C.c_int(n_shared), _ptr(h, torch.bfloat16), _ptr(w_sg, torch.bfloat16),
+                                          _ptr(r.topk_idx, i32), _ptr(r.topk_w, torch.float32), _ptr(r.counts, i32),
+                                          _ptr(r.offsets, i32), _ptr(r.perm, i32), _ptr(r.inv_perm, i32),
+                                          _ptr(out.topk_idx, i32), _ptr(out.topk_w, torch.float32), _ptr(out.counts, i32),
+                                          _ptr(out.offsets, i32), _ptr(out.perm, i32), _ptr(out.inv_perm, i32), _stream())
+    _check(rc, "moe_append_shared")
+    return out

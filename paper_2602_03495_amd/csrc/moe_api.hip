@@ -7,6 +7,9 @@ int moe_predict_impl(const moe_shape *, const void *, const float *, const void 
                      int32_t *, void *, hipStream_t);
 int moe_dense_route_impl(const moe_shape *, int32_t *, int32_t *, int32_t *, hipStream_t);
 int moe_shared_gate_impl(const moe_shape *, const void *, const void *, float *, hipStream_t);
+int moe_append_shared_impl(const moe_shape *, int, const void *, const void *, const int32_t *, const float *, const int32_t *,
+                           const int32_t *, const int32_t *, const int32_t *, int32_t *, float *, int32_t *, int32_t *, int32_t *,
+                           int32_t *, hipStream_t);
 int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
                        const void *, const void *, const uint8_t *, void *, void *, int, hipStream_t);
 int moe_ffn_skinny_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
@@ -151,6 +154,22 @@ int moe_shared_gate(const moe_shape *s, const void *h, const void *w_sg, float *
     if (s == nullptr || s->T < 1 || s->d < 128 || s->d > 8192 || s->d % 128 != 0) return MOE_EINVAL;
     if (!h || !w_sg || !scale || !aligned16(h) || !aligned16(w_sg)) return MOE_EINVAL;
     return moe_shared_gate_impl(s, h, w_sg, scale, (hipStream_t)stream);
+}
+
+int moe_append_shared(const moe_shape *s, int n_shared, const void *h, const void *w_sg, const int32_t *topk_idx,
+                      const float *topk_w, const int32_t *counts, const int32_t *offsets, const int32_t *perm,
+                      const int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts, int32_t *x_offsets,
+                      int32_t *x_perm, int32_t *x_inv_perm, void *stream)
+{
+    int rc = check_shape(s, false);
+    if (rc != MOE_OK) return rc;
+    if (n_shared < 1 || s->N + n_shared > MOE_MAX_EXPERTS || s->k + n_shared > MOE_MAX_TOPK) return MOE_EINVAL;
+    if ((long long)s->T * (s->k + n_shared) >= (1ll << 31)) return MOE_EINVAL;
+    if (!topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    if (!x_topk_idx || !x_topk_w || !x_counts || !x_offsets || !x_perm || !x_inv_perm) return MOE_EINVAL;
+    if (w_sg != nullptr && (h == nullptr || !aligned16(h) || !aligned16(w_sg))) return MOE_EINVAL;
+    return moe_append_shared_impl(s, n_shared, h, w_sg, topk_idx, topk_w, counts, offsets, perm, inv_perm, x_topk_idx, x_topk_w,
+                                  x_counts, x_offsets, x_perm, x_inv_perm, (hipStream_t)stream);
 }
 
 int moe_route_predict(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,

@@ -516,6 +516,64 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const ui
     if (lane == 0) scale[t] = 1.0f / (1.0f + expf(-acc));
 }
 
+// Tables of the layer seen as N + S experts with k + S slots per token: the S always-on experts become experts
+// N .. N + S - 1 and take the last S slots of every token (weight 1, or the sigmoid gate of the token), so that one
+// grouped launch computes routed and shared experts alike.  One wave per token; the routed rows keep their order and
+// only their slot ids move to the wider stride.
+__global__ __launch_bounds__(256) void append_shared_kernel(
+    int T, int d, int N, int k, int S, const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_sg,
+    const int32_t *__restrict__ idx, const float *__restrict__ w, const int32_t *__restrict__ counts,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const int32_t *__restrict__ inv,
+    int32_t *__restrict__ x_idx, float *__restrict__ x_w, int32_t *__restrict__ x_counts, int32_t *__restrict__ x_offsets,
+    int32_t *__restrict__ x_perm, int32_t *__restrict__ x_inv)
+{
+    const int lane = threadIdx.x & 63;
+    const int R = T * k, kx = k + S;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t < T) {
+        float c = 1.0f;
+        if (w_sg != nullptr) {
+            const uint16_t *x = h + (size_t)t * d;
+            float acc = 0.f;
+            for (int j = lane * 8; j < d; j += 512) {
+                uint4 a = *reinterpret_cast<const uint4 *>(x + j);
+                uint4 b = *reinterpret_cast<const uint4 *>(w_sg + j);
+                acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+                acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+                acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+                acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+            }
+            acc = wave_sum(acc);
+            c = 1.0f / (1.0f + expf(-acc));
+        }
+        if (lane < kx) {
+            const int o = t * kx + lane;
+            if (lane < k) {
+                x_idx[o] = idx[t * k + lane];
+                x_w[o] = w[t * k + lane];
+                x_inv[o] = inv[t * k + lane];
+            } else {
+                const int row = R + (lane - k) * T + t;
+                x_idx[o] = N + lane - k;
+                x_w[o] = c;
+                x_inv[o] = row;
+                x_perm[row] = o;
+            }
+        }
+    }
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < R; i += gridDim.x * 256) {
+        const int v = perm[i];
+        x_perm[i] = v + (v / k) * S;
+    }
+    if (blockIdx.x == 0) {
+        for (int e = threadIdx.x; e < N + S; e += 256) {
+            x_counts[e] = e < N ? counts[e] : T;
+            x_offsets[e] = e < N ? offsets[e] : R + (e - N) * T;
+        }
+        if (threadIdx.x == 0) x_offsets[N + S] = R + S * T;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // host side
 static gate_job make_job(const void *gate_w, const float *bias, int norm_mode, int32_t *topk_idx, float *topk_w)
@@ -700,6 +758,18 @@ int moe_shared_gate_impl(const moe_shape *s, const void *h, const void *w_sg, fl
 {
     hipLaunchKernelGGL(shared_gate_kernel, dim3((s->T + 3) / 4), dim3(256), 0, st, s->T, s->d, (const uint16_t *)h,
                        (const uint16_t *)w_sg, scale);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+int moe_append_shared_impl(const moe_shape *s, int n_shared, const void *h, const void *w_sg, const int32_t *topk_idx,
+                           const float *topk_w, const int32_t *counts, const int32_t *offsets, const int32_t *perm,
+                           const int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts,
+                           int32_t *x_offsets, int32_t *x_perm, int32_t *x_inv_perm, hipStream_t st)
+{
+    hipLaunchKernelGGL(append_shared_kernel, dim3((s->T + 3) / 4), dim3(256), 0, st, s->T, s->d, s->N, s->k, n_shared,
+                       (const uint16_t *)h, (const uint16_t *)w_sg, topk_idx, topk_w, counts, offsets, perm, inv_perm, x_topk_idx,
+                       x_topk_w, x_counts, x_offsets, x_perm, x_inv_perm);
     MOE_CHECK_LAUNCH();
     return MOE_OK;
 }

@@ -34,9 +34,12 @@ class LayerWeights:
     sw3: Optional[torch.Tensor] = None
     sw2: Optional[torch.Tensor] = None   # [S,d,Is] packed
     w_sg: Optional[torch.Tensor] = None  # [d] bf16 (sigmoid-gated shared expert)
+    xw1: Optional[torch.Tensor] = None   # [N+S',I,d] packed: routed experts, then the shared ones cut into inner blocks of I
+    xw3: Optional[torch.Tensor] = None
+    xw2: Optional[torch.Tensor] = None   # [N+S',d,I] packed
 
     @staticmethod
-    def upload(gate_w, gate_bias, w1, w3, w2, shared=None, device="cuda") -> "LayerWeights":
+    def upload(gate_w, gate_bias, w1, w3, w2, shared=None, device="cuda", merge_shared=False) -> "LayerWeights":
         """Upload row-major bf16 bit patterns and pack the expert matrices on the device (one time)."""
         def packed(bits):
             return B.moe_pack_weights(to_device_bf16(bits, device))
@@ -48,6 +51,14 @@ class LayerWeights:
             sw1, sw3, sw2, w_sg = shared
             lw.sw1, lw.sw3, lw.sw2 = (packed(a) for a in (sw1, sw3, sw2))
             lw.w_sg = None if w_sg is None else to_device_bf16(w_sg, device)
+            S, Is, d = sw1.shape
+            I = w1.shape[1]
+            if merge_shared and Is % I == 0:
+                # a shared expert of inner size m*I as m experts of inner size I, stored after the routed ones
+                m = Is // I
+                c1, c3 = sw1.reshape(S * m, I, d), sw3.reshape(S * m, I, d)
+                c2 = np.ascontiguousarray(sw2.reshape(S, d, m, I).transpose(0, 2, 1, 3)).reshape(S * m, d, I)
+                lw.xw1, lw.xw3, lw.xw2 = (packed(np.concatenate(p)) for p in ((w1, c1), (w3, c3), (w2, c2)))
         torch.cuda.synchronize()
         return lw
 
@@ -64,6 +75,7 @@ class MoeLayer:
         self.out = torch.empty((T, cfg.d), dtype=torch.bfloat16, device=device)
         self.pred_counts = torch.empty(cfg.N, dtype=torch.int32, device=device)
         self.n_shared = cfg.n_shared
+        self.n_merged = 0
         if cfg.n_shared:
             S = cfg.n_shared
             self.sshape = B.shape(T, cfg.d, S, S, cfg.I_shared, ffn_path)
@@ -75,6 +87,15 @@ class MoeLayer:
             self.shared_scale = (torch.empty(T, dtype=torch.float32, device=device)
                                  if cfg.shared_gate == "sigmoid" else None)
             B.moe_dense_route(self.sshape, self.s_counts, self.s_offsets, self.s_perm)
+            if cfg.I_shared % cfg.I == 0:
+                # the same layer as N + n_merged experts with k + n_merged slots per token (one grouped launch for all)
+                Sm = S * (cfg.I_shared // cfg.I)
+                if cfg.N + Sm <= B.MAX_EXPERTS and cfg.k + Sm <= B.MAX_TOPK:
+                    self.n_merged = Sm
+                    self.xshape = B.shape(T, cfg.d, cfg.N + Sm, cfg.k + Sm, cfg.I, ffn_path)
+                    self.xws = B.alloc_workspace(self.xshape, device)
+                    self.xrouting = B.alloc_routing(self.xshape, device)
+                    self.xy = torch.empty((T * (cfg.k + Sm), cfg.d), dtype=torch.bfloat16, device=device)
 
     def route(self, h, w: LayerWeights, bias=None):
         b = w.gate_bias if bias is None else bias
@@ -111,6 +132,24 @@ class MoeLayer:
         if self.n_shared and with_shared:
             self.shared_ffn(h, w)
         return self.combine(mask, with_shared)
+
+    def merged_mask(self, mask) -> torch.Tensor:
+        """mask [N] over the routed experts (None = all on) -> mask [N + n_merged] with the shared experts on."""
+        on = torch.ones(self.cfg.N + self.n_merged, dtype=torch.uint8, device=self.device)
+        if mask is not None:
+            on[: self.cfg.N].copy_(mask)
+        return on
+
+    def forward_merged(self, h, w: LayerWeights, xmask, bias=None):
+        """The same layer with the shared experts inside the grouped launches: route -> append the shared slots ->
+        one expert FFN over routed and shared experts -> combine.  xmask: merged_mask(mask), or None for all on."""
+        if not self.n_merged or w.xw1 is None:
+            raise B.MoeError("this layer has no shared experts that split into experts of the routed inner size")
+        self.route(h, w, bias)
+        x = B.moe_append_shared(self.shape, self.n_merged, h, w.w_sg if self.shared_scale is not None else None,
+                                self.routing, self.xrouting)
+        B.moe_expert_ffn(self.xshape, h, x.perm, x.offsets, x.counts, w.xw1, w.xw3, w.xw2, xmask, self.xy, self.xws)
+        return B.moe_combine(self.xshape, self.xy, x.topk_idx, x.topk_w, x.inv_perm, xmask, None, 0, None, self.out)
 
     def predict(self, h, res_vec, next_w: LayerWeights, p: int, top_experts, next_bias=None, ws=None):
         """ws: a workspace of its own when the prediction runs concurrently with this layer's other calls."""

@@ -125,3 +125,19 @@ def test_new_entry_points_reject_bad_arguments_before_launching(lib):
     assert rp(p, p, z, 1, p, p, p, p, p, p, C.c_void_p(0x1004), p, z, 2, p, p, p, z) == MOE_EINVAL   # res_vec alignment
     assert rp(p, p, z, 1, p, p, p, p, p, p, p, p, z, 2, p, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
     assert lib.moe_predict_workload(C.byref(s), p, C.c_void_p(0x1004), p, z, 2, p, p, p, z) == MOE_EINVAL
+
+
+def test_append_shared_rejects_bad_arguments_before_launching(lib):
+    s = Shape(16, 256, 8, 2, 512, 0)
+    p = C.c_void_p(0x1000)
+    z = C.c_void_p(0)
+    ap = lambda n_sh, h, wsg, *tables: lib.moe_append_shared(C.byref(s), n_sh, h, wsg, *tables, z)
+    ok = (p,) * 12
+    assert ap(0, z, z, *ok) == MOE_EINVAL                                          # no shared expert
+    assert ap(7, z, z, *ok) == MOE_EINVAL                                          # k + n_shared > 8 slots
+    assert ap(2, z, p, *ok) == MOE_EINVAL                                          # a gate vector without h
+    assert ap(2, C.c_void_p(0x1004), p, *ok) == MOE_EINVAL                         # h misaligned
+    for i in range(12):                                                            # every table pointer is required
+        assert ap(2, z, z, *(ok[:i] + (z,) + ok[i + 1:])) == MOE_EINVAL
+    wide = Shape(16, 256, 127, 2, 512, 0)
+    assert lib.moe_append_shared(C.byref(wide), 2, z, z, *ok, z) == MOE_EINVAL     # N + n_shared > 128 experts

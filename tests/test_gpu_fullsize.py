@@ -35,7 +35,7 @@ def host_and_device(Lm, name):
         _cache.clear()                    # keep one config resident at a time
         torch.cuda.empty_cache()
         hl = make_host_layer(wl.CONFIGS[name])
-        dw = Lm.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2, hl.shared)
+        dw = Lm.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2, hl.shared, merge_shared=True)
         _cache[name] = (hl, dw)
     return _cache[name]
 
@@ -117,6 +117,35 @@ def test_full_size_layer(gpu, name, T):
     zero = L.forward(hd, dw, torch.zeros(cfg.N, dtype=torch.uint8, device="cuda"), with_shared=False)
     torch.cuda.synchronize()
     assert not bool(zero.view(torch.int16).bitwise_and(0x7FFF).any())
+
+
+@pytest.mark.parametrize("name,T", [("deepseek", 16), ("deepseek", 2048), ("qwen15", 1), ("qwen15", 4096)])
+def test_full_size_layer_with_shared_experts_inside_the_grouped_launches(gpu, name, T):
+    B, Lm = gpu
+    cfg = wl.CONFIGS[name]
+    print(f"full size, shared experts appended: {name} T={T}", flush=True)
+    hl, dw = host_and_device(Lm, name)
+    mask = config_mask(cfg, hl)
+    h = wl.hidden_states(cfg, T, draw=T)
+    lg, o_idx, o_w, o_counts = oracle.route(h, hl.gate_w, hl.bias, cfg.k, cfg.norm_mode)
+    L = Lm.MoeLayer(cfg, T)
+    assert L.n_merged == cfg.n_shared * (cfg.I_shared // cfg.I)
+    hd = Lm.to_device_bf16(h)
+    out = L.forward_merged(hd, dw, L.merged_mask(torch.from_numpy(mask).cuda()))
+    torch.cuda.synchronize()
+    r, x = L.routing, L.xrouting
+    ex = check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets), _np(r.perm),
+                       _np(r.inv_perm), cfg.N, cfg.k)
+    x_idx, x_counts = _np(x.topk_idx), _np(x.counts)
+    assert np.array_equal(x_counts, np.bincount(x_idx.ravel(), minlength=cfg.N + L.n_merged))
+    assert np.array_equal(_np(x.perm), np.argsort(x_idx.ravel(), kind="stable"))
+    toks = sample_tokens(T, 24, seed=cfg.seed + T)
+    toks = toks[~ex[toks]]
+    ref = oracle.layer(h, o_idx, o_w, hl.w1, hl.w3, hl.w2, mask, hl.shared, hl.shared_mode, tokens=toks)
+    got = wl.bf16_bits_to_f32(Lm.from_device_bf16(out))[toks]
+    err = rel_err(got, ref)
+    print(f"  sampled {len(toks)} tokens: layer output {err:.2e}", flush=True)
+    assert err <= OUT_TOL, err
 
 
 def test_full_size_mask_additivity_mixtral(gpu):

@@ -412,3 +412,57 @@ def test_route_without_a_workspace_gives_the_same_tables(gpu, name, T):
         assert torch.equal(getattr(ra, f), getattr(rb, f)), f
     assert torch.allclose(ra.topk_w, rb.topk_w, rtol=1e-6, atol=0)
     assert int(rb.counts.sum()) == T * cfg.k
+
+
+# ------------------------------------------------------------------------------------------- shared experts inside the grouped launches
+MERGED = {
+    "deepseek_m": wl.scaled(wl.CONFIGS["deepseek"], d=256, I=128, I_shared=128),    # 2 shared experts, weight 1
+    "qwen15_m": wl.scaled(wl.CONFIGS["qwen15"], d=384, I=128, I_shared=512),        # 1 sigmoid-gated shared expert = 4 x I
+}
+
+
+@pytest.mark.parametrize("name,T", [("deepseek_m", 1), ("deepseek_m", 16), ("deepseek_m", 333), ("qwen15_m", 1),
+                                    ("qwen15_m", 40), ("qwen15_m", 700)])
+def test_shared_experts_appended_to_the_routing_tables(gpu, name, T):
+    B, Lm = gpu
+    cfg = MERGED[name]
+    print(f"merged shared {name} T={T}", flush=True)
+    hl = make_host_layer(cfg)
+    h = wl.hidden_states(cfg, T, draw=T)
+    lg, o_idx, o_w, o_counts = oracle.route(h, hl.gate_w, hl.bias, cfg.k, cfg.norm_mode)
+    dw = Lm.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2, hl.shared, merge_shared=True)
+    L = Lm.MoeLayer(cfg, T)
+    Sm = L.n_merged
+    assert Sm == cfg.n_shared * (cfg.I_shared // cfg.I) and dw.xw1.shape[0] == cfg.N + Sm
+    kx, R = cfg.k + Sm, T * cfg.k
+    hd = Lm.to_device_bf16(h)
+    mask = (np.arange(cfg.N) % 4 != 1).astype(np.uint8)
+    for m in (None, mask):
+        xm = L.merged_mask(None if m is None else torch.from_numpy(m).cuda())
+        out = L.forward_merged(hd, dw, xm)
+        torch.cuda.synchronize()
+        r, x = L.routing, L.xrouting
+        ex = check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
+                           _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
+        x_idx, x_w, x_counts, x_off = _np(x.topk_idx), _np(x.topk_w), _np(x.counts), _np(x.offsets)
+        x_perm, x_inv = _np(x.perm), _np(x.inv_perm)
+        # the routed slots are the oracle's (checked above on the routed tables: here they must be those tables, unchanged)
+        assert np.array_equal(x_idx[:, :cfg.k], _np(r.topk_idx)) and np.array_equal(x_w[:, :cfg.k], _np(r.topk_w))
+        # the shared slots: expert N + j, weight 1 or the oracle's sigmoid gate
+        assert np.array_equal(x_idx[:, cfg.k:], np.tile(cfg.N + np.arange(Sm, dtype=np.int32), (T, 1)))
+        c = oracle.shared_scale(h, hl.shared[3]) if hl.shared_mode == 2 else np.ones(T)
+        assert np.allclose(x_w[:, cfg.k:], np.repeat(c[:, None], Sm, 1), rtol=2e-5, atol=1e-7)
+        # histogram, scan and the stable grouping of the wider tables
+        assert np.array_equal(x_counts, np.bincount(x_idx.ravel(), minlength=cfg.N + Sm))
+        assert np.all(x_counts[cfg.N:] == T) and int(x_counts.sum()) == T * kx
+        assert np.array_equal(x_off, np.concatenate(([0], np.cumsum(x_counts))))
+        assert np.array_equal(x_perm, np.argsort(x_idx.ravel(), kind="stable"))
+        assert np.array_equal(x_inv[x_perm], np.arange(T * kx))
+        # layer output against the oracle's layer with shared experts
+        keep = np.nonzero(~ex)[0].astype(np.int32)
+        ref = oracle.layer(h, o_idx, o_w, hl.w1, hl.w3, hl.w2, m, hl.shared, hl.shared_mode, tokens=keep)
+        got = wl.bf16_bits_to_f32(Lm.from_device_bf16(out))[keep]
+        assert rel_err(got, ref) <= OUT_TOL, rel_err(got, ref)
+        # and against the separate-launch path of the same library (the shared term is rounded to bf16 once per block there)
+        sep = L.forward(hd, dw, None if m is None else torch.from_numpy(m).cuda()).float().cpu().numpy()[keep]
+        assert rel_err(sep, ref) <= OUT_TOL
