@@ -112,8 +112,15 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
             xo[j] = ((uint32_t)r * (uint32_t)I + xc * 8) * 2u;
     }
     const char *xbase = reinterpret_cast<const char *>(MODE == 0 ? xsrc : xsrc + (size_t)row0 * I);
-    uint16_t *xw = &Xs[0][xc >> 2][(tid >> 3) * 32 + (xc & 3) * 8];   // + buffer * 2*TM*32 + j * 64 rows
-    const uint16_t *xrd = &Xs[0][0][li * 32 + lg * 8];               // + buffer * 2*TM*32 + half * TM*32 + t * 16 rows
+    // LDS holds every 16-row x k32 subtile in MFMA fragment order with a swizzle: the 16 bytes of (row i, k chunk g) of
+    // k32 half hf sit in slot 16 g + (i ^ g ^ 8 hf).  A fragment read is then one KB per wave, and the LDS serves a
+    // 16-byte-per-lane read in four passes of 16 lanes -- lanes {0-3, 12-15, 20-23, 24-27} and so on, measured -- which
+    // must hit 16 different 16-byte bank groups: i ^ g keeps that (4 clocks per read instead of 8 for plain rows), while
+    // the 8 chunks of one row, which one store instruction of the loader carries in 8 adjacent lanes, land in 8
+    // different bank groups (16 clocks per store instead of 64 for the unswizzled fragment order).
+    uint16_t *xw = &Xs[0][xc >> 2][(tid >> 7) * 512 + ((xc & 3) * 16 + (((tid >> 3) & 15) ^ (xc & 3) ^ (xc >> 2) * 8)) * 8];   // + buffer * 2*TM*32 + j * 64 rows
+    const uint16_t *xrd0 = &Xs[0][0][(lg * 16 + (li ^ lg)) * 8];       // + buffer * 2*TM*32 + t * 16 rows
+    const uint16_t *xrd1 = &Xs[0][1][(lg * 16 + (li ^ lg ^ 8)) * 8];
 
     f32x4 acc[NF][NTT];
 #pragma unroll
@@ -156,7 +163,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #define XREAD(buf, half)                                                                         \
     do {                                                                                         \
         _Pragma("unroll") for (int t = 0; t < NTT; ++t)                                          \
-            xf[t] = as_frag(*reinterpret_cast<const u32x4 *>(xrd + (buf) * (2 * TM * 32) + (half) * (TM * 32) + t * (16 * 32))); \
+            xf[t] = as_frag(*reinterpret_cast<const u32x4 *>(((half) ? xrd1 : xrd0) + (buf) * (2 * TM * 32) + t * (16 * 32))); \
     } while (0)
     /* token subtile outermost: the first NF MFMAs need only the first LDS read, so the later reads land behind them */ \
 #define MFMAS(set)                                                                               \
