@@ -87,6 +87,34 @@ def median_event_seconds(torch, fn, runs=20, flush=None):
     return sorted(ts)[runs // 2]
 
 
+def library_gemm_yardstick(torch):
+    """Context for the roofline fractions, not part of the path: what the vendor library's dense bf16 GEMM (torch.matmul)
+    reaches on this GPU, (a) on one large GEMM, (b) on one GEMM with the prefill workload's row total, (c) as one GEMM per
+    expert with the workload's rows per expert (up: [rows,d] x [d,2I], down: [rows,I] x [I,d]).  No gather, no SwiGLU."""
+    d, I = 4096, 14336
+    rows = [1540, 379, 283, 550, 165, 126]       # the six masked-on experts of the prefill workload
+    g = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", dtype=torch.float32, generator=g).mul_(0.02).to(torch.bfloat16)
+    w13, w2 = rnd(2 * I, d), rnd(d, I)
+    w13s = [w13] + [rnd(2 * I, d) for _ in rows[1:]]
+    w2s = [w2] + [rnd(d, I) for _ in rows[1:]]
+    xs, acts = [rnd(r, d) for r in rows], [rnd(r, I) for r in rows]
+    xb, xc = rnd(sum(rows), d), rnd(8192, d)
+    frac = lambda flop, sec: flop / sec / PEAK_BF16_MFMA
+    t_big = median_event_seconds(torch, lambda: xc @ w13.t())
+    t_one = median_event_seconds(torch, lambda: xb @ w13.t())
+    t_up = median_event_seconds(torch, lambda: [x @ w.t() for x, w in zip(xs, w13s)])
+    t_dn = median_event_seconds(torch, lambda: [a @ w.t() for a, w in zip(acts, w2s)])
+    rec = {"metric": "vendor-library dense bf16 GEMM, fraction of the MFMA peak (context)", "unit": "fraction", "n_gpus": 1,
+           "dense_8192x4096x28672": {"us": t_big * 1e6, "frac": frac(8192 * 4.0 * d * I, t_big)},
+           "dense_3043x4096x28672": {"us": t_one * 1e6, "frac": frac(sum(rows) * 4.0 * d * I, t_one)},
+           "per_expert_up": {"us": t_up * 1e6, "frac": frac(sum(rows) * 4.0 * d * I, t_up)},
+           "per_expert_down": {"us": t_dn * 1e6, "frac": frac(sum(rows) * 2.0 * d * I, t_dn)}, "rows": rows}
+    log(f"[bench] library GEMM: 8192 rows {rec['dense_8192x4096x28672']['frac']:.3f}, 3043 rows {rec['dense_3043x4096x28672']['frac']:.3f}, "
+        f"per expert up {t_up * 1e6:.0f} us {rec['per_expert_up']['frac']:.3f}, down {t_dn * 1e6:.0f} us {rec['per_expert_down']['frac']:.3f}")
+    return rec
+
+
 def time_graph_replays(torch, L, hd, dw, mask_d, steps, warmup):
     """The same pass captured once in a HIP graph and replayed: removes the host's per-launch cost, which at
     decode sizes is a large share of an eagerly launched step.  Returns wall seconds for `steps` replays."""
@@ -264,6 +292,8 @@ def main():
                          "decode and the mid-sized batches between them) and print one JSON line with all records")
     ap.add_argument("--stack-layers", type=int, default=48)
     ap.add_argument("--stack-steps", type=int, default=256)
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context only: the vendor library's dense bf16 GEMM (torch.matmul) on the prefill workload's shapes")
     ap.add_argument("--calib-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy 5 times (reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -279,6 +309,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.load_library()   # raises if the HIP library has not been built
     torch.cuda.set_device(0)
+
+    if args.library_gemm:
+        print(json.dumps(library_gemm_yardstick(torch)), flush=True)
+        return
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
