@@ -115,6 +115,76 @@ def library_gemm_yardstick(torch):
     return rec
 
 
+def greedy_assignment_demo(torch, B, Lm, wl, pcie_gbs):
+    """Greedy Assignment (Alg. 1) end to end on the Mixtral-shaped layer.  Cost model of Section "Greedy Assignment
+    Strategy": gpu_compute(w) = the expert FFN of this library timed on one expert with w rows; cpu_compute(w) = w times
+    the oracle's time per (token, expert) row on the host cores; an uncached expert pays its weights over the host link.
+    The workload histograms of a prefill and a decode batch then go through moe_expert_times and moe_greedy_assign, the
+    resulting G is used as expert_mask, and the makespan max(T_gpu, T_cpu) is compared with everything on one side and
+    with the best of all 2^N assignments."""
+    import itertools
+    cfg = wl.CONFIGS["mixtral"]
+    W, b = wl.gate_weights(cfg), wl.gate_bias(cfg)
+    w1, w3, w2 = wl.expert_weights(cfg)
+    dw = Lm.LayerWeights.upload(W, b, w1, w3, w2)
+    wmax = 2048
+    # ---- gpu_compute(w): every token sent to experts 0 and 1 by the gate bias, only expert 0 masked on
+    force = torch.zeros(cfg.N, dtype=torch.float32, device="cuda")
+    force[0], force[1] = 1e4, 5e3
+    only0 = torch.zeros(cfg.N, dtype=torch.uint8, device="cuda")
+    only0[0] = 1
+    pts, secs = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048], []
+    for w in pts:
+        L = Lm.MoeLayer(cfg, w)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, w, draw=w))
+        L.route(hd, dw, bias=force)
+        torch.cuda.synchronize()
+        assert int(L.routing.counts[0]) == w
+        secs.append(median_event_seconds(torch, lambda: L.expert_ffn(hd, dw, only0), 10))
+        log(f"[bench] gpu_compute({w:4d} rows) = {secs[-1] * 1e6:8.1f} us")
+    gpu_compute = np.interp(np.arange(wmax + 1), [0] + pts, [0.0] + secs).astype(np.float32)
+    # ---- cpu_compute(w): the oracle's expert rows, timed on a few rows
+    import oracle
+    n = 8
+    h8 = wl.hidden_states(cfg, n)
+    idx8 = np.tile(np.arange(cfg.k, dtype=np.int32), (n, 1))
+    t0 = time.perf_counter()
+    oracle.expert_rows(h8, idx8, w1, w3, w2)
+    row_s = (time.perf_counter() - t0) / (n * cfg.k)
+    cpu_compute = (np.arange(wmax + 1) * row_s).astype(np.float32)
+    trans = 3.0 * cfg.d * cfg.I * 2 / (pcie_gbs * 1e9)
+    log(f"[bench] cpu_compute = {row_s * 1e3:.2f} ms per row on {oracle.num_threads()} threads; transfer of one expert = {trans * 1e3:.2f} ms")
+
+    cached = wl.mask_random(cfg, 6)
+    cases = []
+    for T in (2048, 16):
+        L = Lm.MoeLayer(cfg, T)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
+        L.route(hd, dw)
+        torch.cuda.synchronize()
+        counts = L.routing.counts.cpu().numpy()
+        for what, ca in (("6 of 8 experts cached", cached), ("nothing cached", None)):
+            t_gpu, t_cpu = B.expert_times(counts, ca, trans, gpu_compute, cpu_compute)
+            G, Cc, Tg, Tc = B.greedy_assign(t_gpu, t_cpu)
+            act = [e for e in range(cfg.N) if counts[e] > 0]
+            span = lambda on_gpu: max(sum(float(t_gpu[e]) for e in act if on_gpu[e]), sum(float(t_cpu[e]) for e in act if not on_gpu[e]))
+            best = min(span(dict(zip(act, bits))) for bits in itertools.product((0, 1), repeat=len(act)))
+            md = torch.from_numpy(G).cuda()
+            step = median_event_seconds(torch, lambda: (L.expert_ffn(hd, dw, md), L.combine(md)), 10)
+            rec = {"tokens": T, "cache": what, "counts": counts.tolist(), "G": G.tolist(), "C": Cc.tolist(),
+                   "T_gpu_ms": float(Tg) * 1e3, "T_cpu_ms": float(Tc) * 1e3, "makespan_ms": float(max(Tg, Tc)) * 1e3,
+                   "all_gpu_ms": float(t_gpu.sum()) * 1e3, "all_cpu_ms": float(t_cpu.sum()) * 1e3, "optimum_ms": float(best) * 1e3,
+                   "gpu_share_measured_ms": float(step) * 1e3}
+            log(f"[bench] T={T:4d} {what:22s} counts={counts.tolist()} G={G.tolist()} makespan {rec['makespan_ms']:.2f} ms "
+                f"(all GPU {rec['all_gpu_ms']:.2f}, all CPU {rec['all_cpu_ms']:.2f}, optimum {rec['optimum_ms']:.2f}); "
+                f"GPU share as run: {step * 1e3:.3f} ms")
+            cases.append(rec)
+    return {"metric": "Greedy Assignment (Alg. 1) makespan", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "mixtral-8x7b-shaped layer, prefill 2048 and decode 16 tokens", "pcie_GBps": pcie_gbs},
+            "gpu_compute_us": dict(zip(map(str, pts), (float(x) * 1e6 for x in secs))), "cpu_row_ms": float(row_s) * 1e3,
+            "cpu_threads": oracle.num_threads(), "transfer_ms": float(trans) * 1e3, "cases": cases}
+
+
 def time_graph_replays(torch, L, hd, dw, mask_d, steps, warmup):
     """The same pass captured once in a HIP graph and replayed: removes the host's per-launch cost, which at
     decode sizes is a large share of an eagerly launched step.  Returns wall seconds for `steps` replays."""
@@ -292,6 +362,10 @@ def main():
                          "decode and the mid-sized batches between them) and print one JSON line with all records")
     ap.add_argument("--stack-layers", type=int, default=48)
     ap.add_argument("--stack-steps", type=int, default=256)
+    ap.add_argument("--assign", action="store_true",
+                    help="Greedy Assignment (Alg. 1) on the Mixtral-shaped layer: t_gpu(w) timed on this library's kernels, "
+                         "t_cpu(w) from the timed oracle, masks for the prefill and decode workloads")
+    ap.add_argument("--pcie-gbs", type=float, default=32.0, help="--assign: host-to-device rate behind the transfer time of an uncached expert")
     ap.add_argument("--library-gemm", action="store_true",
                     help="context only: the vendor library's dense bf16 GEMM (torch.matmul) on the prefill workload's shapes")
     ap.add_argument("--calib-copy", action="store_true",
@@ -312,6 +386,10 @@ def main():
 
     if args.library_gemm:
         print(json.dumps(library_gemm_yardstick(torch)), flush=True)
+        return
+
+    if args.assign:
+        print(json.dumps(greedy_assignment_demo(torch, B, Lm, wl, args.pcie_gbs)), flush=True)
         return
 
     if args.calib_copy:
@@ -356,7 +434,7 @@ def main():
         # Workload-Aware Cache Replacement (Alg. 2) replayed over the measured histogram stream, one cache per layer:
         # 64 of 128 experts resident, w_size = 4, u_size = 8; hit rate = share of the routed rows that found their
         # expert resident, against a cache that keeps its initial (lower-half) contents
-        hits = tot = hits_static = 0
+        hits = tot = hits_static = loads = 0
         t_sched = time.perf_counter()
         for l in range(args.stack_layers):
             cache = B.ExpertCache(cfg5.N, range(cfg5.N // 2), 4, 8)
@@ -367,8 +445,27 @@ def main():
                 hits += int(w[cache.on_gpu.astype(bool)].sum())
                 hits_static += int(w[static].sum())
                 tot += int(w.sum())
-                cache.step(w)
+                loads += len(cache.step(w))
         t_sched = time.perf_counter() - t_sched
+        # the comparison policy of Section "Workload-Aware Cache Replacement": least recently used, same capacity and
+        # initial contents; an activated expert that is not resident is loaded at once in place of the one unused longest
+        hits_lru = loads_lru = 0
+        for l in range(args.stack_layers):
+            last = np.full(cfg5.N, -1, np.int64)
+            res_ = np.zeros(cfg5.N, bool)
+            res_[: cfg5.N // 2] = True
+            for t in range(args.stack_steps):
+                w = c[t, l]
+                hits_lru += int(w[res_].sum())
+                used = np.nonzero(w > 0)[0]
+                last[used] = t
+                for e in used[~res_[used]]:
+                    cand = np.nonzero(res_)[0]
+                    victim = cand[np.argmin(last[cand])]
+                    if last[victim] == t:
+                        break                     # everything resident was used in this step
+                    res_[victim], res_[e] = False, True
+                    loads_lru += 1
         hist = {"shape": list(c.shape), "max_workload": int(c.max()), "mean_active_experts": float((c > 0).sum(-1).mean()),
                 "mean_top1_share": float((c.max(-1) / c.sum(-1)).mean()),
                 "first_step_first_layer": c[0, 0].tolist()}
@@ -381,6 +478,9 @@ def main():
                                                    "graph_replay": {"no_prediction": ovg["off"], "inline": ovg["inline"], "side_stream": ovg["side"], "fused_with_routing": ovg["fused"]}},
                "cache_replacement": {"policy": "workload-aware (Alg. 2), 64 of 128 resident, w_size 4, u_size 8",
                                      "hit_rate": hits / tot, "hit_rate_static_cache": hits_static / tot,
+                                     "expert_loads_per_layer_step": loads / (args.stack_layers * args.stack_steps),
+                                     "lru_hit_rate": hits_lru / tot,
+                                     "lru_expert_loads_per_layer_step": loads_lru / (args.stack_layers * args.stack_steps),
                                      "host_us_per_layer_step": t_sched / (args.stack_layers * args.stack_steps) * 1e6},
                "histograms": hist}
         print(json.dumps(out), flush=True)

@@ -207,6 +207,23 @@ def moe_pack_weights(src: torch.Tensor, dst: Optional[torch.Tensor] = None) -> t
     return dst
 
 
+def expert_times(counts, cached, trans_time: float, gpu_compute, cpu_compute):
+    """Per-expert execution times on either side (Section "Greedy Assignment Strategy") from profiled time tables indexed
+    by workload: returns (t_gpu, t_cpu) float32 arrays.  cached: uint8 [N] or None."""
+    import numpy as np
+    c = np.ascontiguousarray(counts, np.int32)
+    g, p = np.ascontiguousarray(gpu_compute, np.float32), np.ascontiguousarray(cpu_compute, np.float32)
+    assert g.size == p.size and g.size >= 1
+    ca = None if cached is None else np.ascontiguousarray(cached, np.uint8)
+    t_gpu, t_cpu = np.zeros(c.size, np.float32), np.zeros(c.size, np.float32)
+    f = C.POINTER(C.c_float)
+    _check(load_library().moe_expert_times(C.c_int(c.size), c.ctypes.data_as(C.POINTER(C.c_int32)),
+                                           None if ca is None else ca.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                           C.c_float(trans_time), g.ctypes.data_as(f), p.ctypes.data_as(f), C.c_int(g.size - 1),
+                                           t_gpu.ctypes.data_as(f), t_cpu.ctypes.data_as(f)), "moe_expert_times")
+    return t_gpu, t_cpu
+
+
 def greedy_assign(t_gpu, t_cpu):
     """Alg. 1 on host arrays: returns (G, C, T_gpu, T_cpu) with G, C as uint8 numpy arrays."""
     import numpy as np
