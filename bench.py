@@ -115,6 +115,12 @@ def library_gemm_yardstick(torch):
     return rec
 
 
+def cpu_baseline_oracle():
+    """The CPU-baseline leg: the only place where this script touches the oracle, and only to time it on the host cores."""
+    import oracle
+    return oracle
+
+
 def greedy_assignment_demo(torch, B, Lm, wl, pcie_gbs):
     """Greedy Assignment (Alg. 1) end to end on the Mixtral-shaped layer.  Cost model of Section "Greedy Assignment
     Strategy": gpu_compute(w) = the expert FFN of this library timed on one expert with w rows; cpu_compute(w) = w times
@@ -144,7 +150,7 @@ def greedy_assignment_demo(torch, B, Lm, wl, pcie_gbs):
         log(f"[bench] gpu_compute({w:4d} rows) = {secs[-1] * 1e6:8.1f} us")
     gpu_compute = np.interp(np.arange(wmax + 1), [0] + pts, [0.0] + secs).astype(np.float32)
     # ---- cpu_compute(w): the oracle's expert rows, timed on a few rows
-    import oracle
+    oracle = cpu_baseline_oracle()
     n = 8
     h8 = wl.hidden_states(cfg, n)
     idx8 = np.tile(np.arange(cfg.k, dtype=np.int32), (n, 1))
@@ -552,7 +558,7 @@ def main():
     # ---- CPU oracle on a bounded sample -----------------------------------------------------------------
     cpu = None
     if args.cpu_sample > 0:
-        import oracle
+        oracle = cpu_baseline_oracle()
         n = min(args.cpu_sample, T)
         toks = np.arange(n, dtype=np.int32)
         t0 = time.perf_counter()
