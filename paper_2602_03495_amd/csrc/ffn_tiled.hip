@@ -31,6 +31,7 @@
 // over the address space; the summation order is a function of (expert, weight tile) only, so results are
 // reproducible.
 #include "moe_common.h"
+#include <stdlib.h>
 
 #define TM MOE_TILE_M     // token rows per tile
 #define NUM_XCD MOE_NUM_XCD
@@ -72,7 +73,7 @@ template <int MODE, int NF, int NTT, int NSETS>
 __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int I, int k, const uint16_t *__restrict__ xsrc,
                                           const int32_t *__restrict__ perm, const uint16_t *__restrict__ wa,
                                           const uint16_t *__restrict__ wb, uint16_t *__restrict__ out, int e, int nt,
-                                          int row0, int nrows)
+                                          int row0, int nrows, int sp, int nsp, float *__restrict__ part, int R)
 {
     constexpr int HF = MODE == 0 ? NF / 2 : NF;           // fragments per matrix per wave
     constexpr int WAVE_COLS = HF * 16;                     // output columns a wave produces
@@ -94,7 +95,8 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     {
         int col = n0 + wave * WAVE_COLS;
         if (col >= NOUT) col = NOUT - WAVE_COLS;           // a wave past the ragged edge recomputes the last columns
-        const size_t mat = (size_t)e * d * I + (size_t)(col >> 4) * rb_stride;
+        // + the first k32 step of this item's share of K (MODE 1 with the K range split over nsp items)
+        const size_t mat = (size_t)e * d * I + (size_t)(col >> 4) * rb_stride + (size_t)sp * (kb_n / nsp) * 512;
         wp0 = reinterpret_cast<const char *>(wa + mat);
         wp1 = MODE == 0 ? reinterpret_cast<const char *>(wb + mat) : wp0;
     }
@@ -111,7 +113,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         else
             xo[j] = ((uint32_t)r * (uint32_t)I + xc * 8) * 2u;
     }
-    const char *xbase = reinterpret_cast<const char *>(MODE == 0 ? xsrc : xsrc + (size_t)row0 * I);
+    const char *xbase = reinterpret_cast<const char *>(MODE == 0 ? xsrc : xsrc + (size_t)row0 * I + (size_t)sp * (kb_n / nsp) * 32);
     // LDS holds every 16-row x k32 subtile in MFMA fragment order with a swizzle: the 16 bytes of (row i, k chunk g) of
     // k32 half hf sit in slot 16 g + (i ^ g ^ 8 hf).  A fragment read is then one KB per wave, and the LDS serves a
     // 16-byte-per-lane read in four passes of 16 lanes -- lanes {0-3, 12-15, 20-23, 24-27} and so on, measured -- which
@@ -128,7 +130,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #pragma unroll
         for (int t = 0; t < NTT; ++t) acc[f][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = kb_n;          // k32 steps (a multiple of NSETS: the launch checks K)
+    const int nk = kb_n / nsp;    // k32 steps of this item (a multiple of NSETS: the launch checks K)
     const int nst = nk / 2;       // k64 stages
     const int st0 = (int)(((unsigned)e * 5u) % (unsigned)nst);   // where this item's K ring starts (per expert: tiles that share rows or weights stay in step)
     static_assert(NSETS == 4 || NSETS == 8, "an even number of stages per unrolled round");
@@ -207,6 +209,19 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     // ---- epilogue: in every 16x16 tile a lane holds weight rows 4*lg + 0..3 (= output columns) of token li
     const int colw = n0 + wave * WAVE_COLS;
     if (colw >= NOUT) return;                               // wave past the ragged edge: its columns were recomputed only
+    if (MODE == 1 && nsp > 1) {
+        // one of nsp partial sums over K: fp32, summed in split order by the finishing pass
+#pragma unroll
+        for (int t = 0; t < NTT; ++t) {
+            const int tr = t * 16 + li;
+            if (tr < nrows) {
+                float *prow = part + ((size_t)sp * R + row0 + tr) * NOUT + colw + 4 * lg;
+#pragma unroll
+                for (int f = 0; f < HF; ++f) *reinterpret_cast<f32x4 *>(prow + f * 16) = acc[f][t];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int t = 0; t < NTT; ++t) {
         const int tr = t * 16 + li;
@@ -236,19 +251,39 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
     const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
     const int32_t *__restrict__ sched, const uint8_t *__restrict__ mask,   // DIRECT: mask instead of a schedule
-    uint16_t *__restrict__ out)                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
+    uint16_t *__restrict__ out,                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
+    int nsp_max, float *__restrict__ part, int R)   // MODE 1: up to nsp_max K splits per tile, partial sums in part [nsp,R,d] fp32
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
+    // The up projection with its widest tile (NF = 4: 256 inner columns) can run its items with half that width instead:
+    // also decided on the device, when even the doubled number of items leaves no compute unit with two of them (measured:
+    // beyond that the narrower items cost more than the fuller launch gains).
+    constexpr bool CAN_NARROW = MODE == 0 && NF == 4;
     constexpr int NT_COLS = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
-    const int n_nt = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;
+    int n_ntc = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;   // column tiles
+    bool narrow = false;
 
-    // ---- which item -------------------------------------------------------------------------------
-    int e, mt, nt;
+    // ---- which item: (expert, token tile, column tile, K split).  The number of K splits follows from the number of
+    // tiles that have work, which only the device knows (counts and mask live there)
+    int e, mt, nt, nsp = 1;
     if (DIRECT) {
         // at most one token tile per expert (T <= 128): no schedule has been built
-        if (!moe_working_item(N, counts, mask, n_nt, blockIdx.x, e, nt)) return;
+        unsigned long long act_lo, act_hi;
+        const int n_work = moe_working_experts(N, counts, mask, act_lo, act_hi);
+        if (MODE == 1) nsp = moe_dev_splits(n_work * n_ntc, nsp_max);
+        if (CAN_NARROW && n_work * n_ntc <= 128) {
+            narrow = true;
+            n_ntc = (I + NT_COLS / 2 - 1) / (NT_COLS / 2);
+        }
+        if (!moe_item_of(act_lo, act_hi, n_ntc * nsp, blockIdx.x, e, nt)) return;
         mt = 0;
     } else {
+        if (MODE == 1) nsp = moe_dev_splits(sched[0] * n_ntc, nsp_max);
+        if (CAN_NARROW && sched[0] * n_ntc <= 128) {
+            narrow = true;
+            n_ntc = (I + NT_COLS / 2 - 1) / (NT_COLS / 2);
+        }
+        const int n_nt = n_ntc * nsp;
         const int total = sched[0] * n_nt;
         const int pid = blockIdx.x;
         if (pid >= total) return;
@@ -261,25 +296,75 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         mt = local % ent.z;
         nt = local / ent.z;
     }
+    const int sp = nt % nsp;      // column tile nt / nsp, K split nt % nsp
+    nt /= nsp;
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;
     nrows = nrows > TM ? TM : nrows;
-#define BODY(n) tile_body<MODE, NF, n, NSETS>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows)
-    if (!DYN) BODY(NTT_MAX);
-    else if (NTT_MAX == 1 || nrows <= 16) BODY(1);
-    else if (NTT_MAX == 2 || nrows <= 32) BODY(2);
-    else if (NTT_MAX == 4 || nrows <= 64) BODY(4);
-    else BODY(8);
-#undef BODY
+#define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
+#define BODIES(nf_)                                                \
+    do {                                                           \
+        if (!DYN) BODY_NF(nf_, NTT_MAX);                           \
+        else if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);     \
+        else if (NTT_MAX == 2 || nrows <= 32) BODY_NF(nf_, 2);     \
+        else if (NTT_MAX == 4 || nrows <= 64) BODY_NF(nf_, 4);     \
+        else BODY_NF(nf_, 8);                                      \
+    } while (0)
+    if constexpr (CAN_NARROW) {
+        if (narrow) {
+            BODIES(2);
+            return;
+        }
+    }
+    BODIES(NF);
+#undef BODIES
+#undef BODY_NF
+}
+
+// y[p,:] = bf16( sum over the K splits, in split order ), when the down projection of this launch split K (the same
+// device-side decision as in ffn_tiled_kernel; nothing to do otherwise: the tiles wrote y themselves)
+__global__ __launch_bounds__(256) void tiled_finish_kernel(int d, int R, int N, int n_ntc, int nsp_max, int direct,
+                                                           const int32_t *__restrict__ sched, const float *__restrict__ partial,
+                                                           const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
+                                                           const uint8_t *__restrict__ mask, uint16_t *__restrict__ y)
+{
+    int tiles;
+    if (direct) {
+        unsigned long long act_lo, act_hi;
+        tiles = moe_working_experts(N, counts, mask, act_lo, act_hi);
+    } else {
+        tiles = sched[0];
+    }
+    const int nsp = moe_dev_splits(tiles * n_ntc, nsp_max);
+    if (nsp == 1) return;
+    const int e = blockIdx.y, j = blockIdx.x;
+    if (j >= counts[e] || (mask != nullptr && mask[e] == 0)) return;
+    const size_t p = (size_t)offsets[e] + j;
+    for (int f = threadIdx.x * 4; f < d; f += 1024) {
+        float4 a = *reinterpret_cast<const float4 *>(partial + p * d + f);
+        for (int ks = 1; ks < nsp; ++ks) {
+            const float4 b = *reinterpret_cast<const float4 *>(partial + ((size_t)ks * R + p) * d + f);
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        uint2 o;
+        o.x = pack_bf16x2(a.x, a.y);
+        o.y = pack_bf16x2(a.z, a.w);
+        *reinterpret_cast<uint2 *>(y + p * d + f) = o;
+    }
 }
 
 template <int MODE, int NF, int NTT, bool DIRECT, int NSETS>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
-                         const uint8_t *mask, uint16_t *out, hipStream_t st)
+                         const uint8_t *mask, uint16_t *out, int nsp_max, float *part, hipStream_t st)
 {
     constexpr int cols = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
-    const long n_nt = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
+    const long n_ntc = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
+    const int R = s->T * s->k;
+    // blocks for the most items the device-side choice of K splits can produce: with every tile at work it takes the
+    // fewest splits that reach 256 items, with fewer tiles at work there are fewer items, so this bound covers both
+    long n_nt = n_ntc * nsp_max;
+    if (MODE == 0 && NF == 4) n_nt = (s->I + cols / 2 - 1) / (cols / 2);   // ... or the half-width items of the up projection
     const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
     // a block sizes its body to its own rows when tiles are sparsely filled on average (under 128 rows per expert);
@@ -289,10 +374,10 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
     if (full_tiles) {
         if constexpr (!DIRECT)
             hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, false, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I,
-                               s->k, s->N, x, perm, offsets, counts, wa, wb, sched, mask, out);
+                               s->k, s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
     } else {
         hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, true, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
-                           s->N, x, perm, offsets, counts, wa, wb, sched, mask, out);
+                           s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
     }
 }
 
@@ -305,11 +390,11 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
 template <int MODE>
 static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16_t *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *counts, const uint16_t *wa, const uint16_t *wb,
-                           const int32_t *sched, const uint8_t *mask, uint16_t *out, hipStream_t st)
+                           const int32_t *sched, const uint8_t *mask, uint16_t *out, int nsp_max, float *part, hipStream_t st)
 {
     const int K = MODE == 0 ? s->d : s->I;
-    const bool deep = K % 256 == 0 && K >= 2048;          // a short K does not pay for the longer prologue
-#define GO(NF_, NTT_, D_, NS_) launch_tiled<MODE, NF_, NTT_, D_, NS_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, st)
+    const bool deep = K % (256 * nsp_max) == 0 && K >= 2048;   // a short K does not pay for the longer prologue
+#define GO(NF_, NTT_, D_, NS_) launch_tiled<MODE, NF_, NTT_, D_, NS_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st)
 #define GO3(NTT_, D_)                                                          \
     do {                                                                       \
         if constexpr (MODE == 1) {                                             \
@@ -354,7 +439,7 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
             MOE_CHECK_LAUNCH();
         }
         dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
-                          (const uint16_t *)w3, sched, expert_mask, act, st);
+                          (const uint16_t *)w3, sched, expert_mask, act, 1, nullptr, st);
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_DOWN) {
@@ -362,9 +447,21 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
         // columns, then 256 columns), else the narrowest (128 columns)
         const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
                        : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
+        // and when even that leaves compute units idle -- few experts with rows, or few of them masked on -- the K range
+        // of every tile is split over up to nsp_max items (decided on the device, which knows counts and mask)
+        const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
+        int nsp_max = moe_tiled_down_max_splits(s);
+        if (getenv("MOE_NOSPLIT")) nsp_max = 1;
+        float *part = (float *)((char *)workspace + L.partial);
         dispatch_tiled<1>(s, nf, max_mt, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
-                          (const uint16_t *)nullptr, sched, expert_mask, (uint16_t *)y, st);
+                          (const uint16_t *)nullptr, sched, expert_mask, (uint16_t *)y, nsp_max, part, st);
         MOE_CHECK_LAUNCH();
+        if (nsp_max > 1) {
+            const int max_rows = s->T < (int)R ? s->T : (int)R;
+            hipLaunchKernelGGL(tiled_finish_kernel, dim3(max_rows, N), dim3(256), 0, st, d, (int)R, N, n_ntc, nsp_max,
+                               s->T <= TM ? 1 : 0, sched, part, offsets, counts, expert_mask, (uint16_t *)y);
+            MOE_CHECK_LAUNCH();
+        }
     }
     return MOE_OK;
 }

@@ -88,13 +88,22 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g * __built
 // contiguous run of the compacted item list (expert-major), and the item's expert is found by rank among the set
 // bits.  Returns false for a block beyond the list.  All 64 lanes of the wave must call it.
 #define MOE_NUM_XCD 8
-__device__ __forceinline__ bool moe_working_item(int N, const int32_t *__restrict__ counts, const uint8_t *__restrict__ mask,
-                                                 int per_expert, int pid, int &e, int &local)
+__device__ __forceinline__ int moe_working_experts(int N, const int32_t *__restrict__ counts, const uint8_t *__restrict__ mask,
+                                                   unsigned long long &act_lo, unsigned long long &act_hi)
 {
     const int l = threadIdx.x & 63;
     const bool on_lo = l < N && counts[l] > 0 && (mask == nullptr || mask[l] != 0);
     const bool on_hi = l + 64 < N && counts[l + 64] > 0 && (mask == nullptr || mask[l + 64] != 0);
-    const unsigned long long act_lo = __ballot(on_lo), act_hi = __ballot(on_hi);
+    act_lo = __ballot(on_lo);
+    act_hi = __ballot(on_hi);
+    return __popcll(act_lo) + __popcll(act_hi);
+}
+
+// the item of block pid among (working experts) x per_expert items, or false beyond the list
+__device__ __forceinline__ bool moe_item_of(unsigned long long act_lo, unsigned long long act_hi, int per_expert, int pid, int &e,
+                                            int &local)
+{
+    const int l = threadIdx.x & 63;
     const int n_lo = __popcll(act_lo);
     const int total = (n_lo + __popcll(act_hi)) * per_expert;
     if (pid >= total) return false;
@@ -116,6 +125,23 @@ __device__ __forceinline__ bool moe_working_item(int N, const int32_t *__restric
     return true;
 }
 
+__device__ __forceinline__ bool moe_working_item(int N, const int32_t *__restrict__ counts, const uint8_t *__restrict__ mask,
+                                                 int per_expert, int pid, int &e, int &local)
+{
+    unsigned long long act_lo, act_hi;
+    moe_working_experts(N, counts, mask, act_lo, act_hi);
+    return moe_item_of(act_lo, act_hi, per_expert, pid, e, local);
+}
+
+// K splits of the tiled down projection, decided on the device from the number of tile items that have work: the
+// smallest power of two, at most nsp_max, that brings the launch to 256 items (one per compute unit)
+__host__ __device__ __forceinline__ int moe_dev_splits(int items, int nsp_max)
+{
+    int nsp = 1;
+    while (nsp < nsp_max && items * nsp < 256) nsp *= 2;
+    return nsp;
+}
+
 #define MOE_CHECK_LAUNCH()                       \
     do {                                         \
         if (hipGetLastError() != hipSuccess)     \
@@ -127,7 +153,7 @@ static inline size_t moe_align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // ---- workspace layout (one per shape; every entry point carves what it needs from offset 0) ----
 struct moe_ws_layout {
     size_t act;        // [T*k, I] bf16 inner activations
-    size_t partial;    // [nsplit, T*k, d] fp32 split-K partial sums of the skinny down projection
+    size_t partial;    // [nsplit, T*k, d] fp32 split-K partial sums of the down projection (skinny path, or the tiled path's K splits)
     size_t sched;      // tile schedule of the tiled path
     size_t route;      // routing scratch: folded bias [N], idx [T*k], w [T*k] (prediction), 2 x logits [max(T,16), N] (gate product and selection in separate launches)
     size_t total;
@@ -143,6 +169,20 @@ static inline int moe_skinny_nsplit(int K)
 {
     int per_block = MOE_SKINNY_WAVES * MOE_SKINNY_MAX_STEPS * 32;
     return (K + per_block - 1) / per_block;
+}
+
+// Tiled down projection: the most K splits a launch may use (1 = never split).  Every split keeps at least 32 k32 steps, a
+// multiple of 8; the fp32 partial sums [nsp, T*k, d] must fit 64 MB.  Whether a launch splits at all is decided on
+// the device (moe_dev_splits): only when the experts that have rows and are masked on leave compute units without a tile.
+static inline int moe_tiled_down_max_splits(const moe_shape *s)
+{
+    if (s->T <= MOE_SKINNY_MAX_T) return 1;
+    const int steps = s->I / 32;
+    int nsp = 1;
+    while (nsp < 8 && steps % (2 * nsp * 8) == 0 && steps / (2 * nsp) >= 32 &&
+           (size_t)(2 * nsp) * s->T * s->k * s->d * 4 <= ((size_t)64 << 20))
+        nsp *= 2;
+    return nsp;
 }
 
 // one [max(T, 16), N] fp32 block of gate logits (the gate product and the selection are separate launches when the
@@ -161,7 +201,10 @@ static inline moe_ws_layout moe_ws(const moe_shape *s)
     off += moe_align256(R * (size_t)s->I * 2);
     L.partial = off;
     size_t Rs = R < (size_t)MOE_SKINNY_MAX_T * MOE_MAX_TOPK ? R : (size_t)MOE_SKINNY_MAX_T * MOE_MAX_TOPK;
-    off += moe_align256((size_t)moe_skinny_nsplit(s->I) * Rs * s->d * 4);
+    size_t part = (size_t)moe_skinny_nsplit(s->I) * Rs * s->d * 4;
+    const int nsp = moe_tiled_down_max_splits(s);
+    if (nsp > 1 && (size_t)nsp * R * s->d * 4 > part) part = (size_t)nsp * R * s->d * 4;
+    off += moe_align256(part);
     L.sched = off;
     off += moe_align256(((size_t)R / MOE_TILE_M + MOE_MAX_EXPERTS + 8) * 16);
     L.route = off;

@@ -169,6 +169,20 @@ def test_scaled_layers_skinny_path(gpu, name, T):
     _run_layer(B, Lm, cfg, T, [mask, None], B.FFN_AUTO)
 
 
+@pytest.mark.parametrize("T,n_on", [(40, 1), (40, 2), (100, 3), (200, 1), (200, 2), (300, 8)])
+def test_few_working_experts_take_split_k_and_half_width_tiles(gpu, T, n_on):
+    # with few experts masked on, the tiled kernels decide on the device to split the K range of the down projection
+    # (fp32 partial sums + a finishing pass) and to run the up projection on half-width tiles; with all experts on they
+    # do neither.  I = 8192 allows up to 8 splits (T = 40: single token tiles; T = 200, 300: scheduled tiles).
+    B, Lm = gpu
+    cfg = wl.scaled(wl.CONFIGS["mixtral"], d=512, I=8192)
+    print(f"few working experts T={T} on={n_on}", flush=True)
+    _, _, _, counts = oracle.route(wl.hidden_states(cfg, T), wl.gate_weights(cfg), wl.gate_bias(cfg), cfg.k, cfg.norm_mode)
+    mask = np.zeros(cfg.N, np.uint8)
+    mask[np.argsort(-counts, kind="stable")[:n_on]] = 1
+    _run_layer(B, Lm, cfg, T, [mask], B.FFN_AUTO)
+
+
 def test_skinny_split_k_down_projection(gpu):
     # inner size above 4096 makes the down projection split K over blocks and finish in a second kernel
     B, Lm = gpu
