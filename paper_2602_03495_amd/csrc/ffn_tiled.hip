@@ -31,7 +31,6 @@
 // over the address space; the summation order is a function of (expert, weight tile) only, so results are
 // reproducible.
 #include "moe_common.h"
-#include <stdlib.h>
 
 #define TM MOE_TILE_M     // token rows per tile
 #define NUM_XCD MOE_NUM_XCD
@@ -450,8 +449,7 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
         // and when even that leaves compute units idle -- few experts with rows, or few of them masked on -- the K range
         // of every tile is split over up to nsp_max items (decided on the device, which knows counts and mask)
         const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
-        int nsp_max = moe_tiled_down_max_splits(s);
-        if (getenv("MOE_NOSPLIT")) nsp_max = 1;
+        const int nsp_max = moe_tiled_down_max_splits(s);
         float *part = (float *)((char *)workspace + L.partial);
         dispatch_tiled<1>(s, nf, max_mt, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
                           (const uint16_t *)nullptr, sched, expert_mask, (uint16_t *)y, nsp_max, part, st);
