@@ -102,10 +102,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_up_kernel(
     }
 }
 
-// y[p, f] (or a split-K partial of it) = W2_e[f,:] . act[p,:]
+// y[p, f] (or a split-K partial of it) = W2_e[f,:] . act[p,:].  A block takes nchunks consecutive K chunks of
+// steps_per_block k32 steps each (4 waves x at most MAXS steps in registers), one after the other, accumulating in
+// registers; the grid carries nsplit such blocks per row block.
 template <int MAXS, int RT, bool DIRECT>
 __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
-    int d, int I, int R, int N, int row_blocks, int nsplit, int steps_per_block, const uint16_t *__restrict__ act,
+    int d, int I, int R, int N, int row_blocks, int nsplit, int nchunks, int steps_per_block, const uint16_t *__restrict__ act,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts, const uint16_t *__restrict__ w2,
     const uint8_t *__restrict__ mask, uint16_t *__restrict__ y, float *__restrict__ partial)
 {
@@ -119,39 +121,43 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_down_kernel(
     const int i = lane & 15, g = lane >> 4;
     const int off = offsets[e];
     const int total = I >> 5;
-    const int b0 = by * steps_per_block;
-    int bn = total - b0;
-    bn = bn > steps_per_block ? steps_per_block : bn;
     const int per = (steps_per_block + SK_WAVES - 1) / SK_WAVES;
-    const int s0 = b0 + wave * per;
-    int ns = b0 + bn - s0;
-    ns = ns < 0 ? 0 : (ns > per ? per : ns);
-
-    u32x4 xf[MAXS];
-    {
-        const bool valid = i < c;
-        load_x_frags<MAXS>(xf, act + (size_t)(off + (valid ? i : 0)) * I, valid, s0, ns, g);
-    }
+    const bool valid = i < c;
+    const uint16_t *xrow = act + (size_t)(off + (valid ? i : 0)) * I;
     const int f0 = bx * (16 * RT);
-    const int last = ns > 0 ? ns - 1 : 0;
+
+    f32x4 acc[RT];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        int rb = (f0 >> 4) + rt;                            // 16-row block of W2
-        if (rb * 16 >= d) rb = (d >> 4) - 1;
-        const uint16_t *p2 = w2 + (size_t)e * d * I + ((size_t)rb * total + s0) * 512 + lane * 8;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (ns > 0) {
+    for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int b0 = (by * nchunks + ch) * steps_per_block;
+        int bn = total - b0;
+        bn = bn > steps_per_block ? steps_per_block : bn;
+        const int s0 = b0 + wave * per;
+        int ns = b0 + bn - s0;
+        ns = ns < 0 ? 0 : (ns > per ? per : ns);
+        if (ns <= 0) continue;
+        u32x4 xf[MAXS];
+        load_x_frags<MAXS>(xf, xrow, valid, s0, ns, g);
+        const int last = ns - 1;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            int rb = (f0 >> 4) + rt;                            // 16-row block of W2
+            if (rb * 16 >= d) rb = (d >> 4) - 1;
+            const uint16_t *p2 = w2 + (size_t)e * d * I + ((size_t)rb * total + s0) * 512 + lane * 8;
             u32x4 a[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; ++s)
                 a[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p2 + (s < ns ? s : last) * 512));
 #pragma unroll
             for (int s = 0; s < MAXS; ++s)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[s]), as_frag(xf[s]), acc, 0, 0, 0);
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(a[s]), as_frag(xf[s]), acc[rt], 0, 0, 0);
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave][rt][lane * 4 + r] = acc[r];
     }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][rt][lane * 4 + r] = acc[rt][r];
     __syncthreads();
     const int el = threadIdx.x;
     const int src = el >> 2, r = el & 3;
@@ -217,16 +223,16 @@ static void launch_up(int rt, dim3 grid, hipStream_t st, int d, int k, int I, in
 }
 
 template <int MAXS, bool DIRECT>
-static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, int N, int rb, int nsplit, int spb,
+static void launch_down(int rt, dim3 grid, hipStream_t st, int d, int I, int R, int N, int rb, int nsplit, int nchunks, int spb,
                         const uint16_t *act, const int32_t *offsets, const int32_t *counts, const uint16_t *w2,
                         const uint8_t *mask, uint16_t *y, float *partial)
 {
     if (rt == 4)
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 4, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 4, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, nchunks, spb, act, offsets, counts, w2, mask, y, partial);
     else if (rt == 2)
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 2, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 2, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, nchunks, spb, act, offsets, counts, w2, mask, y, partial);
     else
-        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 1, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, spb, act, offsets, counts, w2, mask, y, partial);
+        hipLaunchKernelGGL((skinny_down_kernel<MAXS, 1, DIRECT>), grid, dim3(SK_THREADS), 0, st, d, I, R, N, rb, nsplit, nchunks, spb, act, offsets, counts, w2, mask, y, partial);
 }
 
 int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
@@ -264,16 +270,22 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         return moe_ffn_tiled_impl(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, MOE_FFN_STAGE_DOWN, st);
     if (stages & MOE_FFN_STAGE_DOWN) {
         const int total = I >> 5;
-        const int nsplit = moe_skinny_nsplit(I);
-        const int spb = (total + nsplit - 1) / nsplit;
+        const int nchunk_all = moe_skinny_nsplit(I);         // K chunks of at most 4096
+        const int spb = (total + nchunk_all - 1) / nchunk_all;
         const int per = (spb + SK_WAVES - 1) / SK_WAVES;
         const int tiles = (d + 15) / 16;
+        // All K chunks inside one block (no partial sums, no finishing pass) when one 16-row tile per block, without a
+        // K split, already gives every compute unit two blocks: single-token batches (-5 % on the whole step).  With
+        // more rows the count of working experts is only an upper bound on the host, and a launch sized for it with
+        // whole-K blocks runs short of blocks when few experts are masked on (measured 2x slower): one chunk per block.
+        const bool in_block = (long)tiles * est_active >= 512 && pick_rt(tiles, est_active) == 1;
+        const int nsplit = in_block ? 1 : nchunk_all, nchunks = in_block ? nchunk_all : 1;
         const int rt = pick_rt(tiles * nsplit, est_active);
         const int rbk = (tiles + rt - 1) / rt;               // row blocks per working expert
         dim3 grid((unsigned)(rbk * nsplit * est_active));
         const uint16_t *p2 = (const uint16_t *)w2;
         uint16_t *yp = (uint16_t *)y;
-#define DN(n, direct) case n: launch_down<4 * n, direct>(rt, grid, st, d, I, R, N, rbk, nsplit, spb, act, offsets, counts, p2, expert_mask, yp, partial); break;
+#define DN(n, direct) case n: launch_down<4 * n, direct>(rt, grid, st, d, I, R, N, rbk, nsplit, nchunks, spb, act, offsets, counts, p2, expert_mask, yp, partial); break;
         if (nsplit == 1) {
             switch ((per + 3) / 4) { DN(1, true) DN(2, true) DN(3, true) DN(4, true) DN(5, true) DN(6, true) DN(7, true) DN(8, true) default: return MOE_EUNSUPPORTED; }
             MOE_CHECK_LAUNCH();
