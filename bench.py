@@ -29,7 +29,7 @@ PEAK_BF16_MFMA = 2.5e15   # flop/s, MI355X dense bf16 matrix peak
 PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
 # HBM bytes per launch of the dominant kernels (fetched + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this script, scaled by what the same counters read for a plain 1 GiB copy (see profiles/)
-TRAFFIC_PREFILL_UP = 2.003e9 + 87.3e6
+TRAFFIC_PREFILL_UP = 2.023e9 + 87.3e6
 TRAFFIC_DECODE_UP = {1: 470.0e6, 16: 1.175e9 + 0.75e6}
 
 
