@@ -244,7 +244,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 
 // NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
 // body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
-template <int MODE, int NF, int NTT_MAX, bool DIRECT, bool DYN, int NSETS>
+template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS>
 __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, int N, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
@@ -303,8 +303,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
 #define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
 #define BODIES(nf_)                                                \
     do {                                                           \
-        if (!DYN) BODY_NF(nf_, NTT_MAX);                           \
-        else if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);     \
+        if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);          \
         else if (NTT_MAX == 2 || nrows <= 32) BODY_NF(nf_, 2);     \
         else if (NTT_MAX == 4 || nrows <= 64) BODY_NF(nf_, 4);     \
         else BODY_NF(nf_, 8);                                      \
@@ -366,18 +365,8 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
     if (MODE == 0 && NF == 4) n_nt = (s->I + cols / 2 - 1) / (cols / 2);   // ... or the half-width items of the up projection
     const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
-    // a block sizes its body to its own rows when tiles are sparsely filled on average (under 128 rows per expert);
-    // with fuller tiles the single full-size body is the faster code
-    bool full_tiles = false;
-    if constexpr (!DIRECT) full_tiles = (long)s->T * s->k >= (long)TM * s->N;
-    if (full_tiles) {
-        if constexpr (!DIRECT)
-            hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, false, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I,
-                               s->k, s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
-    } else {
-        hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, true, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
-                           s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
-    }
+    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
+                       s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
 }
 
 // Weight fragments per wave (NF), 16-row token subtiles per tile (NTT) and weight register sets (NSETS).  An expert
