@@ -306,6 +306,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);          \
         else if (NTT_MAX == 2 || nrows <= 32) BODY_NF(nf_, 2);     \
         else if (NTT_MAX == 4 || nrows <= 64) BODY_NF(nf_, 4);     \
+        else if (nrows <= 96) BODY_NF(nf_, 6);                     \
         else BODY_NF(nf_, 8);                                      \
     } while (0)
     if constexpr (CAN_NARROW) {
