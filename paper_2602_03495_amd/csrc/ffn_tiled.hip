@@ -310,6 +310,11 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         else BODY_NF(nf_, 8);                                      \
     } while (0)
     if constexpr (CAN_NARROW) {
+        // a ragged last column tile that fits a half-width item runs as one (I = 1408: five items of 256 + one of 128)
+        if (!narrow && nt == n_ntc - 1 && I % NT_COLS != 0 && I % NT_COLS <= NT_COLS / 2) {
+            narrow = true;
+            nt *= 2;
+        }
         if (narrow) {
             BODIES(2);
             return;
