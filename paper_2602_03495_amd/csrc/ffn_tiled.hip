@@ -68,7 +68,7 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
 // Weight tile of a block: 8 waves x NF fragments x 16 rows.  NTT = 16-row token subtiles computed (rows past
 // nrows are clamped copies whose results are dropped).
-template <int MODE, int NF, int NTT, int NSETS>
+template <int MODE, int NF, int NTT, int NSETS, bool FENCED>
 __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int I, int k, const uint16_t *__restrict__ xsrc,
                                           const int32_t *__restrict__ perm, const uint16_t *__restrict__ wa,
                                           const uint16_t *__restrict__ wb, uint16_t *__restrict__ out, int e, int nt,
@@ -173,17 +173,27 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
             _Pragma("unroll") for (int f = 0; f < NF; ++f)                                       \
                 acc[f][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(wr[set][f]), xf[t], acc[f][t], 0, 0, 0); \
     } while (0)
+    // FENCED: the compiler may not move the loads and LDS reads of a stage across its MFMA groups (measured: the wide
+    // down-projection tile over a long K runs 4-6 % faster that way, short-K launches 4-8 % slower)
+#define FENCE()                                                                                  \
+    do {                                                                                         \
+        if (FENCED) __builtin_amdgcn_sched_barrier(0);                                           \
+    } while (0)
     // one stage: k32 steps in weight sets ws_ and ws_ + 1; its token rows are in LDS buffer buf
 #define STAGE(buf, ws_)                                                                          \
     do {                                                                                         \
         __builtin_amdgcn_s_waitcnt(0xC07F);      /* lgkmcnt(0): this thread's LDS writes of the stage have landed */ \
         __builtin_amdgcn_s_barrier();                                                            \
+        FENCE();                                                                                 \
         XLOAD(buf, 0);                            /* two stages ahead; its register set is in LDS now */          \
         WLOAD(((ws_) + NSETS - 1) % NSETS, 0);                                                   \
         XREAD(buf, 0);                                                                           \
+        FENCE();                                                                                 \
         MFMAS(ws_);                                                                              \
+        FENCE();                                                                                 \
         WLOAD(ws_, 0);                            /* = set (ws_ + NSETS) % NSETS */              \
         XREAD(buf, 1);                                                                           \
+        FENCE();                                                                                 \
         MFMAS(((ws_) + 1) % NSETS);                                                              \
         XSTORE((buf) ^ 1);                        /* the next stage -> the other LDS buffer */   \
     } while (0)
@@ -199,6 +209,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         for (int u = 0; u < NSETS; u += 2) STAGE((u >> 1) & 1, u);
     }
 #undef STAGE
+#undef FENCE
 #undef MFMAS
 #undef XREAD
 #undef XSTORE
@@ -244,7 +255,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 
 // NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
 // body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
-template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS>
+template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS, bool FENCED>
 __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     int d, int I, int k, int N, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
@@ -300,7 +311,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int row0 = offsets[e] + mt * TM;
     int nrows = counts[e] - mt * TM;
     nrows = nrows > TM ? TM : nrows;
-#define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
+#define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS, FENCED>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
 #define BODIES(nf_)                                                \
     do {                                                           \
         if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);          \
@@ -357,7 +368,7 @@ __global__ __launch_bounds__(256) void tiled_finish_kernel(int d, int R, int N, 
     }
 }
 
-template <int MODE, int NF, int NTT, bool DIRECT, int NSETS>
+template <int MODE, int NF, int NTT, bool DIRECT, int NSETS, bool FENCED>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
                          const uint8_t *mask, uint16_t *out, int nsp_max, float *part, hipStream_t st)
@@ -371,7 +382,7 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
     if (MODE == 0 && NF == 4) n_nt = (s->I + cols / 2 - 1) / (cols / 2);   // ... or the half-width items of the up projection
     const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
-    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
+    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS, FENCED>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
                        s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
 }
 
@@ -388,22 +399,28 @@ static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16
 {
     const int K = MODE == 0 ? s->d : s->I;
     const bool deep = K % (256 * nsp_max) == 0 && K >= 2048;   // a short K does not pay for the longer prologue
-#define GO(NF_, NTT_, D_, NS_) launch_tiled<MODE, NF_, NTT_, D_, NS_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st)
+#define GO(NF_, NTT_, D_, NS_, F_) launch_tiled<MODE, NF_, NTT_, D_, NS_, F_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st)
 #define GO3(NTT_, D_)                                                          \
     do {                                                                       \
         if constexpr (MODE == 1) {                                             \
             if (nf == 1) {                                                     \
-                if (deep) GO(1, NTT_, D_, 8);                                  \
-                else GO(1, NTT_, D_, 4);                                       \
+                if (deep) GO(1, NTT_, D_, 8, false);                                  \
+                else GO(1, NTT_, D_, 4, false);                                       \
                 break;                                                         \
             }                                                                  \
             if (nf == 2) {                                                     \
-                if (deep) GO(2, NTT_, D_, 8);                                  \
-                else GO(2, NTT_, D_, 4);                                       \
+                if (deep) GO(2, NTT_, D_, 8, false);                                  \
+                else GO(2, NTT_, D_, 4, false);                                       \
                 break;                                                         \
             }                                                                  \
         }                                                                      \
-        GO(4, NTT_, D_, 4);                                                    \
+        if constexpr (MODE == 1 && !D_) {                                      \
+            if (K >= 8192) {                                                   \
+                GO(4, NTT_, D_, 4, true);                                      \
+                break;                                                         \
+            }                                                                  \
+        }                                                                      \
+        GO(4, NTT_, D_, 4, false);                                             \
     } while (0)
     if (s->T <= 16) GO3(1, true);
     else if (s->T <= 32) GO3(2, true);
