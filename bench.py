@@ -358,7 +358,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--decode-steps", type=int, default=50)
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--stack", action="store_true",
                     help="run the Qwen3-30B-A3B-shaped decode stack instead (48 layers, 256 steps, batch 16, AR(1) routing) "
