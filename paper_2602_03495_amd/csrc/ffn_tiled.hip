@@ -185,6 +185,24 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     do {                                                                                         \
         if (FENCED || (MODE == 0 && NF == 4)) __builtin_amdgcn_sched_barrier(0);                 \
     } while (0)
+    // Issue order asked of the scheduler for the full-size up-projection body (8 LDS fragment reads, 32 MFMAs and 6 or 4
+    // global loads per half stage): two fragment reads ahead, then one read and one load after every 4 MFMAs.  Measured
+    // inside one run: 5 % faster at 8192 tokens, where most tiles are full, the same at 2048.
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)     /* 0x008 MFMA, 0x020 global load, 0x100 LDS read */
+#define PIPE_HALF(n_loads)                                                                       \
+    do {                                                                                         \
+        if (MODE == 0 && NF == 4 && NTT == 8) {                                                  \
+            SGB(0x100, 2);                                                                       \
+            _Pragma("unroll") for (int i_ = 0; i_ < 6; ++i_) {                                   \
+                SGB(0x008, 4);                                                                   \
+                SGB(0x100, 1);                                                                   \
+                if (i_ < (n_loads)) SGB(0x020, 1);                                               \
+            }                                                                                    \
+            SGB(0x008, 8);                                                                       \
+        }                                                                                        \
+    } while (0)
+#define PIPE_FIRST() PIPE_HALF(6)       /* token loads of the stage + the weights of one step */
+#define PIPE_SECOND() PIPE_HALF(4)
     // one stage: k32 steps in weight sets ws_ and ws_ + 1; its token rows are in LDS buffer buf
 #define STAGE(buf, ws_)                                                                          \
     do {                                                                                         \
@@ -196,11 +214,13 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         XREAD(buf, 0);                                                                           \
         FENCE();                                                                                 \
         MFMAS(ws_);                                                                              \
+        PIPE_FIRST();                                                                            \
         FENCE_MID();                                                                             \
         WLOAD(ws_, 0);                            /* = set (ws_ + NSETS) % NSETS */              \
         XREAD(buf, 1);                                                                           \
         FENCE();                                                                                 \
         MFMAS(((ws_) + 1) % NSETS);                                                              \
+        PIPE_SECOND();                                                                           \
         XSTORE((buf) ^ 1);                        /* the next stage -> the other LDS buffer */   \
     } while (0)
 
@@ -215,6 +235,10 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         for (int u = 0; u < NSETS; u += 2) STAGE((u >> 1) & 1, u);
     }
 #undef STAGE
+#undef PIPE_SECOND
+#undef PIPE_FIRST
+#undef PIPE_HALF
+#undef SGB
 #undef FENCE_MID
 #undef FENCE
 #undef MFMAS
