@@ -274,13 +274,13 @@ int moe_ffn_skinny_impl(const moe_shape *s, const void *h, const int32_t *perm, 
         const int spb = (total + nchunk_all - 1) / nchunk_all;
         const int per = (spb + SK_WAVES - 1) / SK_WAVES;
         const int tiles = (d + 15) / 16;
-        // All K chunks inside one block (no partial sums, no finishing pass) when one 16-row tile per block, without a
-        // K split, already gives every compute unit two blocks: single-token batches (-5 % on the whole step).  With
-        // more rows the count of working experts is only an upper bound on the host, and a launch sized for it with
-        // whole-K blocks runs short of blocks when few experts are masked on (measured 2x slower): one chunk per block.
-        const bool in_block = (long)tiles * est_active >= 512 && pick_rt(tiles, est_active) == 1;
+        // All K chunks inside one block of one 16-row tile (no partial sums, no finishing pass) for batches of at most
+        // 8 routed rows: 1 token 135 -> 129 us per step, 4 tokens 38 -> 34 / 54 -> 48 / 78 -> 74 us for the down
+        // projection with 1 / 2 / 3 experts at work.  With more rows a block's token fragments, re-read per chunk and per
+        // block, outweigh the saved pass (16 tokens, 7 experts at work: 148 -> 160 us): one chunk per block there.
+        const bool in_block = (long)tiles * est_active >= 512 && R <= 8;
         const int nsplit = in_block ? 1 : nchunk_all, nchunks = in_block ? nchunk_all : 1;
-        const int rt = pick_rt(tiles * nsplit, est_active);
+        const int rt = in_block ? 1 : pick_rt(tiles * nsplit, est_active);
         const int rbk = (tiles + rt - 1) / rt;               // row blocks per working expert
         dim3 grid((unsigned)(rbk * nsplit * est_active));
         const uint16_t *p2 = (const uint16_t *)w2;
