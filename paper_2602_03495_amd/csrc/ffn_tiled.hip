@@ -36,32 +36,83 @@
 #define NUM_XCD MOE_NUM_XCD
 #define TILED_THREADS 512
 
-// sched layout: int32 hdr[4] = {n_token_tiles, 0, 0, 0}; then int4 per token tile {expert, first_tile, n_tiles_of_expert, 0}
-__global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, const int32_t *__restrict__ counts,
-                                                                        const uint8_t *__restrict__ mask,
-                                                                        int32_t *__restrict__ sched)
+// Tile tables, one per projection: int32 hdr[4] = {n_token_tiles, tile height, 0, 0}; then int4 per token tile
+// {expert, first_tile, n_tiles_of_expert, 0}.  The up projection uses 128-row tiles.  The down projection has few
+// items (8 column tiles of 512 per token tile at d = 4096), so the number of rounds the launch needs on 256 compute
+// units moves its duration in steps: 27 token tiles are 216 items, one round with 40 units idle, and 30 tiles of 112
+// rows are 240 items, still one round of shorter items.  The tile height of the down projection is therefore chosen
+// here, on the device, from the workloads: 128, 112 or 96 rows, whichever gives the smallest (rounds x item time),
+// with an item's time taken as proportional to (height + 64): its weight loads do not shrink with the tile.
+__device__ __forceinline__ int sched_cost(int tiles, int n_ntc, int tm)
 {
-    __shared__ int nmt[MOE_MAX_EXPERTS];
-    __shared__ int first[MOE_MAX_EXPERTS];
-    const int e = threadIdx.x;
-    int n = 0;
-    if (e < N && counts[e] > 0 && (mask == nullptr || mask[e] != 0)) n = (counts[e] + TM - 1) / TM;
-    nmt[e] = n;
+    const int items = tiles * n_ntc;
+    const int rounds2 = items <= 512 ? 2 * ((items + 255) / 256) : (2 * items + 255) / 256 + 1;   // twice the rounds; beyond two rounds the last one fills unevenly anyway
+    return rounds2 * (tm + 64);
+}
+
+__device__ __forceinline__ int wave_sum_int(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MOE_WAVE);
+    return v;
+}
+
+// exclusive prefix sum over the 128 threads of the block (two waves); *total receives the sum
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wave_total /* LDS, 2 ints */, int *total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < MOE_WAVE; o <<= 1) {
+        const int t = __shfl_up(incl, o, MOE_WAVE);
+        if (lane >= o) incl += t;
+    }
+    if (lane == MOE_WAVE - 1) wave_total[w] = incl;
     __syncthreads();
+    *total = wave_total[0] + wave_total[1];
+    return incl - v + (w == 1 ? wave_total[0] : 0);
+}
+
+__global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, const int32_t *__restrict__ counts,
+                                                                        const uint8_t *__restrict__ mask, int n_ntc_down,
+                                                                        int32_t *__restrict__ sched_up,
+                                                                        int32_t *__restrict__ sched_down)
+{
+    __shared__ int wsum[3][2], wtot[2][2];
+    const int e = threadIdx.x, w = e >> 6;
+    const int c = (e < N && counts[e] > 0 && (mask == nullptr || mask[e] != 0)) ? counts[e] : 0;
+    const int n128 = (c + 127) / 128, n112 = (c + 111) / 112, n96 = (c + 95) / 96;
+    const int s128 = wave_sum_int(n128), s112 = wave_sum_int(n112), s96 = wave_sum_int(n96);
+    if ((e & 63) == 0) {
+        wsum[0][w] = s128;
+        wsum[1][w] = s112;
+        wsum[2][w] = s96;
+    }
+    __syncthreads();
+    // every thread takes the same decision from the same totals
+    const int t128 = wsum[0][0] + wsum[0][1], t112 = wsum[1][0] + wsum[1][1], t96 = wsum[2][0] + wsum[2][1];
+    int tm = 128, best = sched_cost(t128, n_ntc_down, 128);
+    if (t128 * n_ntc_down >= 256) {                         // below that the K range is split instead
+        const int c112 = sched_cost(t112, n_ntc_down, 112), c96 = sched_cost(t96, n_ntc_down, 96);
+        if (c112 < best) { best = c112; tm = 112; }
+        if (c96 < best) { best = c96; tm = 96; }
+    }
+    const int n_dn = tm == 128 ? n128 : tm == 112 ? n112 : n96;
+    int tot_up, tot_dn;
+    const int first_up = block_exclusive_scan(n128, wtot[0], &tot_up);
+    const int first_dn = block_exclusive_scan(n_dn, wtot[1], &tot_dn);
     if (e == 0) {
-        int run = 0;
-        for (int j = 0; j < N; ++j) {
-            first[j] = run;
-            run += nmt[j];
-        }
-        sched[0] = run;
-        sched[1] = sched[2] = sched[3] = 0;
+        sched_up[0] = tot_up;
+        sched_up[1] = TM;
+        sched_up[2] = sched_up[3] = 0;
+        sched_down[0] = tot_dn;
+        sched_down[1] = tm;
+        sched_down[2] = sched_down[3] = 0;
     }
-    __syncthreads();
-    if (e < N) {
-        int4 *tab = reinterpret_cast<int4 *>(sched + 4);
-        for (int j = 0; j < n; ++j) tab[first[e] + j] = make_int4(e, first[e], n, 0);
-    }
+    int4 *tab = reinterpret_cast<int4 *>(sched_up + 4);
+    for (int j = 0; j < n128; ++j) tab[first_up + j] = make_int4(e, first_up, n128, 0);
+    tab = reinterpret_cast<int4 *>(sched_down + 4);
+    for (int j = 0; j < n_dn; ++j) tab[first_dn + j] = make_int4(e, first_dn, n_dn, 0);
 }
 
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
@@ -339,9 +390,10 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     }
     const int sp = nt % nsp;      // column tile nt / nsp, K split nt % nsp
     nt /= nsp;
-    const int row0 = offsets[e] + mt * TM;
-    int nrows = counts[e] - mt * TM;
-    nrows = nrows > TM ? TM : nrows;
+    const int tmk = (DIRECT || MODE == 0) ? TM : sched[1];      // token rows per tile of this launch
+    const int row0 = offsets[e] + mt * tmk;
+    int nrows = counts[e] - mt * tmk;
+    nrows = nrows > tmk ? tmk : nrows;
 #define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS, FENCED>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
 #define BODIES(nf_)                                                \
     do {                                                           \
@@ -349,6 +401,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         else if (NTT_MAX == 2 || nrows <= 32) BODY_NF(nf_, 2);     \
         else if (NTT_MAX == 4 || nrows <= 64) BODY_NF(nf_, 4);     \
         else if (nrows <= 96) BODY_NF(nf_, 6);                     \
+        else if (MODE == 1 && nrows <= 112) BODY_NF(nf_, 7);       \
         else BODY_NF(nf_, 8);                                      \
     } while (0)
     if constexpr (CAN_NARROW) {
@@ -470,14 +523,20 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     const long R = (long)s->T * k;
     moe_ws_layout L = moe_ws(s);
     uint16_t *act = (uint16_t *)((char *)workspace + L.act);
-    int32_t *sched = (int32_t *)((char *)workspace + L.sched);
-    const long max_mt = R / TM + (N < R ? N : R);
+    int32_t *sched = (int32_t *)((char *)workspace + L.sched);                     // up projection's tile table
+    int32_t *sched_down = sched + moe_sched_table_bytes(s) / 4;
+    const long max_mt = R / TM + (N < R ? N : R), max_mt_down = R / MOE_TILE_M_MIN + (N < R ? N : R);
     // token tiles to expect: every expert that can be non-empty has one, large experts have several
     const long est_mt = (R + TM - 1) / TM > (N < R ? N : R) ? (R + TM - 1) / TM : (N < R ? N : R);
 
+    // the down projection's tile shape (needed by the schedule, which the up stage builds for both)
+    const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
+                   : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
+    const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
     if (stages & MOE_FFN_STAGE_UP) {
         if (s->T > TM) {
-            hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, sched);
+            hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, n_ntc, sched,
+                               sched_down);
             MOE_CHECK_LAUNCH();
         }
         dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
@@ -485,22 +544,19 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_DOWN) {
-        // the widest weight tile that still leaves every compute unit a block (512
-        // columns, then 256 columns), else the narrowest (128 columns)
-        const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
-                       : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
-        // and when even that leaves compute units idle -- few experts with rows, or few of them masked on -- the K range
-        // of every tile is split over up to nsp_max items (decided on the device, which knows counts and mask)
-        const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
+        // nf: the widest weight tile that still leaves every compute unit a block (512 columns, then 256 columns), else
+        // the narrowest (128 columns); and when even that leaves compute units idle -- few experts with rows, or few of
+        // them masked on -- the K range of every tile is split over up to nsp_max items (decided on the device, which
+        // knows counts and mask)
         const int nsp_max = moe_tiled_down_max_splits(s);
         float *part = (float *)((char *)workspace + L.partial);
-        dispatch_tiled<1>(s, nf, max_mt, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
-                          (const uint16_t *)nullptr, sched, expert_mask, (uint16_t *)y, nsp_max, part, st);
+        dispatch_tiled<1>(s, nf, max_mt_down, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
+                          (const uint16_t *)nullptr, sched_down, expert_mask, (uint16_t *)y, nsp_max, part, st);
         MOE_CHECK_LAUNCH();
         if (nsp_max > 1) {
             const int max_rows = s->T < (int)R ? s->T : (int)R;
             hipLaunchKernelGGL(tiled_finish_kernel, dim3(max_rows, N), dim3(256), 0, st, d, (int)R, N, n_ntc, nsp_max,
-                               s->T <= TM ? 1 : 0, sched, part, offsets, counts, expert_mask, (uint16_t *)y);
+                               s->T <= TM ? 1 : 0, sched_down, part, offsets, counts, expert_mask, (uint16_t *)y);
             MOE_CHECK_LAUNCH();
         }
     }

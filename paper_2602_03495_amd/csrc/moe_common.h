@@ -162,7 +162,8 @@ struct moe_ws_layout {
 #define MOE_SKINNY_MAX_T 16
 #define MOE_SKINNY_WAVES 4          // waves per block on the skinny path
 #define MOE_SKINNY_MAX_STEPS 32     // 32-wide K steps a wave may hold in registers (K <= 1024 per wave)
-#define MOE_TILE_M 128              // token rows per tile on the tiled path
+#define MOE_TILE_M 128              // token rows per tile on the tiled path (the down projection may choose 112 or 96 on the device)
+#define MOE_TILE_M_MIN 96
 #define MOE_SKINNY_DOWN_MIN_I 2048  // decode-sized down projections with I up to this run on the tiled kernel
 
 static inline int moe_skinny_nsplit(int K)
@@ -183,6 +184,12 @@ static inline int moe_tiled_down_max_splits(const moe_shape *s)
            (size_t)(2 * nsp) * s->T * s->k * s->d * 4 <= ((size_t)64 << 20))
         nsp *= 2;
     return nsp;
+}
+
+// one tile table of the tiled path: int32 hdr[4] + one int4 per token tile, sized for the smallest tile height
+static inline size_t moe_sched_table_bytes(const moe_shape *s)
+{
+    return moe_align256(((size_t)s->T * s->k / MOE_TILE_M_MIN + MOE_MAX_EXPERTS + 8) * 16);
 }
 
 // one [max(T, 16), N] fp32 block of gate logits (the gate product and the selection are separate launches when the
@@ -206,7 +213,7 @@ static inline moe_ws_layout moe_ws(const moe_shape *s)
     if (nsp > 1 && (size_t)nsp * R * s->d * 4 > part) part = (size_t)nsp * R * s->d * 4;
     off += moe_align256(part);
     L.sched = off;
-    off += moe_align256(((size_t)R / MOE_TILE_M + MOE_MAX_EXPERTS + 8) * 16);
+    off += 2 * moe_sched_table_bytes(s);              // one table for the up projection, one for the down projection
     L.route = off;
     off += moe_align256(MOE_MAX_EXPERTS * 4) + 2 * moe_align256(R * 4) + 2 * moe_logits_scratch_bytes(s);
     L.total = off;
