@@ -25,11 +25,15 @@
 // L2) works on a contiguous run of items ordered expert-major, weight tile, token tile: the token tiles that
 // share a weight tile run side by side on one XCD (measured: the same items spread round-robin over the XCDs
 // run up to 40 % slower, even with one token tile per expert).
-// Tiles are rarely full away from large prefill batches: the launch bounds the 16-row subtiles by T, and when
-// the average expert has fewer than 128 rows each block runs the body sized for its own row count.
-// Each item walks K as a ring starting at a tile-dependent offset, which spreads concurrently running tiles
-// over the address space; the summation order is a function of (expert, weight tile) only, so results are
-// reproducible.
+// Tiles are rarely full: the launch bounds the 16-row subtiles by T and every block runs the body sized for its own
+// row count (16, 32, 64, 96, 112 or 128 rows).
+// What only the device knows (counts and mask) also shapes the launch there: with few working tiles the up projection
+// switches to half-width items and the down projection splits the K range of its tiles over several items (fp32 partial
+// sums, summed in split order by tiled_finish_kernel); with many, the schedule kernel picks the token-tile height of
+// the down projection so that its items fill whole rounds of compute units.
+// Each item walks K as a ring starting at an expert-dependent offset, so that the token tiles that share a weight tile
+// stay in step (started at different points they run 18 % slower); the summation order is a function of the expert
+// and of the number of K splits only, so results are reproducible for given inputs.
 #include "moe_common.h"
 
 #define TM MOE_TILE_M     // token rows per tile
