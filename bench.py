@@ -316,6 +316,39 @@ def survey_mid(torch, B, Lm, wl, name, Ts=(32, 64, 128, 256, 512, 1024), steps=2
     return out
 
 
+def survey_few_experts(torch, B, Lm, wl, Ts=(4, 16, 32, 128, 256), ons=(1, 2, 4, 8), steps=15):
+    """Mixtral-shaped layer with only the n most loaded experts masked on (the usual case when most experts live on the
+    host): up and down projection separately, as fractions of the HBM peak of the working experts' weights."""
+    cfg = wl.CONFIGS["mixtral"]
+    w1, w3, w2 = wl.expert_weights(cfg)
+    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2)
+    out = []
+    for T in Ts:
+        L = Lm.MoeLayer(cfg, T)
+        hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
+        L.route(hd, dw)
+        torch.cuda.synchronize()
+        counts = L.routing.counts.cpu().numpy()
+        order = np.argsort(-counts, kind="stable")
+        r = L.routing
+        for n_on in ons:
+            mask = np.zeros(cfg.N, np.uint8)
+            mask[order[:n_on]] = 1
+            md = torch.from_numpy(mask).cuda()
+            active = int(((counts > 0) & (mask > 0)).sum())
+            rec = {"tokens": T, "experts_on": n_on, "active_experts": active}
+            for stage, sn, per in ((B.STAGE_UP, "up", 4.0), (B.STAGE_DOWN, "down", 2.0)):
+                t = median_event_seconds(torch, lambda: B.moe_expert_ffn_stage(L.shape, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3,
+                                                                                 dw.w2, md, L.y, L.ws, stage), steps)
+                rec[sn + "_us"], rec[sn + "_hbm_frac"] = t * 1e6, per * cfg.d * cfg.I * active / t / PEAK_HBM
+            log(f"[bench] mixtral   T={T:5d} experts on {n_on} (working {active}) | up {rec['up_us']:7.1f} us {rec['up_hbm_frac']:.3f} | "
+                f"down {rec['down_us']:7.1f} us {rec['down_hbm_frac']:.3f}")
+            out.append(rec)
+    del dw
+    torch.cuda.empty_cache()
+    return out
+
+
 def survey_rows_per_expert(torch, B, Lm, wl, steps=20):
     """The Mixtral-shaped prefill batch under three routings that differ only in rows per expert (the gate bias is the
     workload's Zipf bias, zero, or +-20 so that two experts take every token): MFMA fraction of either projection."""
@@ -417,7 +450,8 @@ def main():
             mid += survey_mid(torch, B, Lm, wl, name)
         print(json.dumps({"metric": "MoE-layer step time by shape", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": "all layer shapes: prefill, decode and mid-sized batches"},
-                          "steps": recs, "mid_sized": mid, "rows_per_expert": survey_rows_per_expert(torch, B, Lm, wl)}), flush=True)
+                          "steps": recs, "mid_sized": mid, "few_experts_on": survey_few_experts(torch, B, Lm, wl),
+                          "rows_per_expert": survey_rows_per_expert(torch, B, Lm, wl)}), flush=True)
         return
 
     if args.stack:

@@ -156,7 +156,9 @@ int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const
  * The same computation in two separately launchable halves, for callers that want to time or overlap them:
  * MOE_FFN_STAGE_UP writes the bf16 inner activations silu(W1 x) * (W3 x) of all rows into the workspace,
  * MOE_FFN_STAGE_DOWN multiplies them by W2 into y.  A DOWN call must follow an UP call with the same
- * arguments and workspace on the same stream.  MOE_FFN_STAGE_ALL is moe_expert_ffn.
+ * arguments and workspace on the same stream; one that does not stays within its buffers (every call
+ * builds its own tile tables from counts and expert_mask) but multiplies whatever activations the
+ * workspace holds.  MOE_FFN_STAGE_ALL is moe_expert_ffn.
  */
 #define MOE_FFN_STAGE_UP   1
 #define MOE_FFN_STAGE_DOWN 2

@@ -339,6 +339,15 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     }
 }
 
+// Whether the up projection runs its items at half width: twice as many items, each about 0.6 of the time (measured),
+// so it pays when the rounds the launch needs on 256 compute units do not double: up to 128 items (one round either
+// way), or just above a whole number of rounds (280 items: 2 rounds of wide items against 3 of narrow ones).
+__device__ __forceinline__ bool up_items_narrow(int items)
+{
+    const int wide = (items + 255) / 256, narrow = (2 * items + 255) / 256;
+    return narrow * 3 < wide * 5;
+}
+
 // NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
 // body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
 template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS, bool FENCED>
@@ -352,8 +361,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
     // The up projection with its widest tile (NF = 4: 256 inner columns) can run its items with half that width instead:
-    // also decided on the device, when even the doubled number of items leaves no compute unit with two of them (measured:
-    // beyond that the narrower items cost more than the fuller launch gains).
+    // also decided on the device (up_items_narrow).
     constexpr bool CAN_NARROW = MODE == 0 && NF == 4;
     constexpr int NT_COLS = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
     int n_ntc = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;   // column tiles
@@ -367,7 +375,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         unsigned long long act_lo, act_hi;
         const int n_work = moe_working_experts(N, counts, mask, act_lo, act_hi);
         if (MODE == 1) nsp = moe_dev_splits(n_work * n_ntc, nsp_max);
-        if (CAN_NARROW && n_work * n_ntc <= 128) {
+        if (CAN_NARROW && up_items_narrow(n_work * n_ntc)) {
             narrow = true;
             n_ntc = (I + NT_COLS / 2 - 1) / (NT_COLS / 2);
         }
@@ -375,7 +383,7 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         mt = 0;
     } else {
         if (MODE == 1) nsp = moe_dev_splits(sched[0] * n_ntc, nsp_max);
-        if (CAN_NARROW && sched[0] * n_ntc <= 128) {
+        if (CAN_NARROW && up_items_narrow(sched[0] * n_ntc)) {
             narrow = true;
             n_ntc = (I + NT_COLS / 2 - 1) / (NT_COLS / 2);
         }
@@ -537,12 +545,14 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
                    : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
     const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
+    // The tile tables are built at the start of every call, also of one that runs the down stage alone: that call then
+    // never reads a table that an earlier call did not build or built from other counts or another mask.
+    if (s->T > TM) {
+        hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, n_ntc, sched,
+                           sched_down);
+        MOE_CHECK_LAUNCH();
+    }
     if (stages & MOE_FFN_STAGE_UP) {
-        if (s->T > TM) {
-            hipLaunchKernelGGL(tile_schedule_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, st, N, counts, expert_mask, n_ntc, sched,
-                               sched_down);
-            MOE_CHECK_LAUNCH();
-        }
         dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
                           (const uint16_t *)w3, sched, expert_mask, act, 1, nullptr, st);
         MOE_CHECK_LAUNCH();

@@ -183,6 +183,27 @@ def test_few_working_experts_take_split_k_and_half_width_tiles(gpu, T, n_on):
     _run_layer(B, Lm, cfg, T, [mask], B.FFN_AUTO)
 
 
+@pytest.mark.parametrize("T", [16, 40, 300])
+def test_down_stage_alone_builds_its_own_tile_tables(gpu, T):
+    # a down-stage call that no up-stage call preceded must not read tile tables from the workspace: with every workspace
+    # byte set to 1 (table entries would be 16843009, activations 2.4e-38) it multiplies those activations and returns
+    B, Lm = gpu
+    cfg = SMALL["mixtral_s"]
+    print(f"down stage alone T={T}", flush=True)
+    hl = make_host_layer(cfg)
+    dw = _upload(Lm, hl)
+    L = Lm.MoeLayer(cfg, T)
+    hd = Lm.to_device_bf16(wl.hidden_states(cfg, T))
+    L.route(hd, dw)
+    L.ws.fill_(1)
+    L.y.fill_(1.0)
+    r = L.routing
+    B.moe_expert_ffn_stage(L.shape, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, None, L.y, L.ws, B.STAGE_DOWN)
+    torch.cuda.synchronize()
+    y = wl.bf16_bits_to_f32(Lm.from_device_bf16(L.y))
+    assert np.all(np.abs(y) < 1e-30)
+
+
 def test_skinny_split_k_down_projection(gpu):
     # inner size above 4096 makes the down projection split K over blocks and finish in a second kernel
     B, Lm = gpu
