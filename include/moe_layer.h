@@ -135,7 +135,7 @@ int moe_pack_weights(int n_mats, int rows, int K, const void *src, void *dst, vo
 
 /*
  * Expert FFNs of the experts placed on this GPU (the experts with G_i = 1 in Section "Greedy
- * Assignment Strategy"; "each activated expert calculates the corresponding output using x",
+ * Assignment Strategy"; every selected expert is applied to the token's hidden state x,
  * Section "Mixture of Experts (MoE)").  For every expert e with expert_mask[e] != 0 and
  * counts[e] > 0, and each of its rows p in [offsets[e], offsets[e+1]):
  *

@@ -16,7 +16,7 @@
  *   oracle_top_p       the p highest-workload predicted experts chosen for prefetching
  *                      (Section "Residual-Based Prefetching", last sentence before its figure).
  *   oracle_expert_rows E(x)_i for one (token, expert) pair: a SwiGLU feed-forward network
- *                      W2 (silu(W1 x) * (W3 x)); the paper only says "typically implemented as FFN".
+ *                      W2 (silu(W1 x) * (W3 x)); the paper only names a feed-forward network as the usual choice.
  *   oracle_layer       Eq. 2 restricted to the experts with G_i = 1 (the assignment vector of
  *                      Section "Greedy Assignment Strategy", mutual-exclusion constraint), plus the
  *                      always-on shared experts of the model table in "Experimental Setup".
