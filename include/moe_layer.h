@@ -147,6 +147,9 @@ int moe_pack_weights(int n_mats, int rows, int K, const void *src, void *dst, vo
  * moe_dense_route); w1, w3: [N,I,d] bf16 and w2: [N,d,I] bf16, all three PACKED by moe_pack_weights;
  * expert_mask [N] uint8 (NULL = all on);
  * y [T*k,d] bf16 out, in permuted row order: all [device].
+ * The host cannot see the tables, so they are trusted: the kernels index h, y and the workspace with perm,
+ * offsets and counts unchecked, and tables that do not describe a routing of T*k rows (offsets[e] + counts[e]
+ * <= T*k, perm a permutation of 0 .. T*k-1) lead outside the buffers.  Only host-visible arguments are validated.
  */
 int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                    const int32_t *counts, const void *w1, const void *w3, const void *w2,
