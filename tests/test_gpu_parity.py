@@ -169,7 +169,7 @@ def test_scaled_layers_skinny_path(gpu, name, T):
     _run_layer(B, Lm, cfg, T, [mask, None], B.FFN_AUTO)
 
 
-@pytest.mark.parametrize("T,n_on", [(40, 1), (40, 2), (100, 3), (200, 1), (200, 2), (300, 8)])
+@pytest.mark.parametrize("T,n_on", [(40, 1), (40, 2), (100, 3), (128, 7), (200, 1), (200, 2), (200, 5), (300, 8)])
 def test_few_working_experts_take_split_k_and_half_width_tiles(gpu, T, n_on):
     # with few experts masked on, the tiled kernels decide on the device to split the K range of the down projection
     # (fp32 partial sums + a finishing pass) and to run the up projection on half-width tiles; with all experts on they
