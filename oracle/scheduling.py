@@ -9,9 +9,12 @@ Readings where the paper is silent or at odds with itself:
     are evicted; the text is followed.
   * Alg. 2 tests `i mod w_size == 0`, which would fire on the very first token; the text says "after processing a
     window of w_size tokens", so the replacement happens when (i + 1) mod w_size == 0.
-  * The paper always swaps u_size experts; here a pair is swapped only while the incoming expert's score is larger
-    than the outgoing one's (a swap that cannot raise the cached workload is skipped).
-  * Equal scores: lower expert index first, on both sides.
+  * Equal scores: lower expert index first, on both sides.  When fewer than u_size experts are on one side, as many
+    as both sides have are exchanged.
+
+Alg. 2 and the paragraph before it exchange u_size experts at every window end, whatever their scores: that is what
+`WorkloadAwareCache` does by default.  `guarded=True` selects a variant that is NOT the paper's: a pair is exchanged
+only while the incoming expert's score is larger than the outgoing one's.
 """
 from __future__ import annotations
 
@@ -72,8 +75,8 @@ def optimal_assign(t_gpu: Sequence[float], t_cpu: Sequence[float]):
 class WorkloadAwareCache:
     """Alg. 2 for one MoE layer."""
 
-    def __init__(self, N: int, expert_on_gpu: Sequence[int], w_size: int, u_size: int):
-        self.N, self.w_size, self.u_size = N, w_size, u_size
+    def __init__(self, N: int, expert_on_gpu: Sequence[int], w_size: int, u_size: int, guarded: bool = False):
+        self.N, self.w_size, self.u_size, self.guarded = N, w_size, u_size, guarded
         self.s = [0] * N
         self.expert_on_gpu = sorted(expert_on_gpu)
         self.expert_on_cpu = [e for e in range(N) if e not in set(expert_on_gpu)]
@@ -87,8 +90,8 @@ class WorkloadAwareCache:
         if (self.i + 1) % self.w_size == 0:
             cpu_trans = sorted(self.expert_on_cpu, key=lambda e: (-self.s[e], e))[: self.u_size]   # highest scores off the GPU
             gpu_evict = sorted(self.expert_on_gpu, key=lambda e: (self.s[e], e))[: self.u_size]    # lowest scores on the GPU
-            for inc, out in zip(cpu_trans, gpu_evict):
-                if self.s[inc] <= self.s[out]:
+            for inc, out in zip(cpu_trans, gpu_evict):                      # the i-th evicted makes room for the i-th loaded
+                if self.guarded and self.s[inc] <= self.s[out]:
                     break
                 swaps.append((out, inc))
             for out, inc in swaps:

@@ -74,34 +74,72 @@ def test_expert_times_cost_model():
 
 
 def test_cache_hand_trace():
-    (cfg, init, steps, swaps1, after1, swaps2), = list(golden("cache"))
+    (cfg, init, steps, swaps1, after1, swaps2, after2, swaps2_guarded), = list(golden("cache"))
     N, w_size, u_size = (int(x) for x in cfg.split())
-    cache = sch.WorkloadAwareCache(N, [int(x) for x in init.split()], w_size, u_size)
     wl_steps = [[int(x) for x in s.split()] for s in steps.split(";")]
-    out = [cache.step(w) for w in wl_steps[:4]]
-    assert out[:3] == [[], [], []]
-    assert out[3] == [tuple(int(x) for x in p.split(">")) for p in swaps1.split()]
-    assert cache.expert_on_gpu == [int(x) for x in after1.split()]
-    assert cache.s == [0] * N
-    out2 = [cache.step(w) for w in wl_steps[4:]]
-    assert swaps2 == "none" and out2 == [[], [], [], []]
-    assert cache.expert_on_gpu == [int(x) for x in after1.split()]
+    pairs = lambda txt: [] if txt == "none" else [tuple(int(x) for x in p.split(">")) for p in txt.split()]
+    for guarded, want2, want_after2 in ((False, swaps2, after2), (True, swaps2_guarded, after1)):
+        cache = sch.WorkloadAwareCache(N, [int(x) for x in init.split()], w_size, u_size, guarded=guarded)
+        out = [cache.step(w) for w in wl_steps[:4]]
+        assert out[:3] == [[], [], []]
+        assert out[3] == pairs(swaps1)                                   # window 1 is the same under both
+        assert cache.expert_on_gpu == [int(x) for x in after1.split()]
+        assert cache.s == [0] * N
+        out2 = [cache.step(w) for w in wl_steps[4:]]
+        assert out2[:3] == [[], [], []] and out2[3] == pairs(want2)
+        assert cache.expert_on_gpu == [int(x) for x in want_after2.split()]
+
+
+def test_cache_always_exchanges_u_size_experts():
+    """Alg. 2 as printed: at every window end exactly min(u_size, on, off) experts change sides, the evicted ones are
+    the lowest-score experts that were on the GPU, the loaded ones the highest-score experts that were off it."""
+    rng = random.Random(19)
+    for trial in range(40):
+        N = rng.choice([4, 8, 16])
+        n = rng.randint(1, N - 1)
+        w_size, u_size = rng.choice([1, 2, 4]), rng.choice([1, 2, 3, 8])
+        cache = sch.WorkloadAwareCache(N, rng.sample(range(N), n), w_size, u_size)
+        for i in range(24):
+            w = [rng.randint(0, 5) for _ in range(N)]
+            before_on, before_off = list(cache.expert_on_gpu), list(cache.expert_on_cpu)
+            s_after = [a + b for a, b in zip(cache.s, w)]
+            swaps = cache.step(w)
+            if (i + 1) % w_size:
+                assert swaps == []
+                continue
+            u = min(u_size, n, N - n)
+            assert len(swaps) == u
+            ev, ld = [a for a, _ in swaps], [b for _, b in swaps]
+            assert set(ev) <= set(before_on) and set(ld) <= set(before_off)
+            # nothing left on the GPU scored below an evicted expert, nothing left off it scored above a loaded one
+            assert all(s_after[x] >= max(s_after[y] for y in ev) for x in before_on if x not in ev)
+            assert all(s_after[x] <= min(s_after[y] for y in ld) for x in before_off if x not in ld)
+            assert sorted(cache.expert_on_gpu) == sorted((set(before_on) - set(ev)) | set(ld))
+            assert len(cache.expert_on_gpu) == n and cache.s == [0] * N
 
 
 def test_cache_invariants_and_convergence():
     rng = random.Random(3)
-    N, n = 16, 6
-    cache = sch.WorkloadAwareCache(N, list(range(n)), w_size=4, u_size=3)
+    N = 16
     hot = [9, 11, 12, 13, 14, 15]
-    for i in range(64):
-        w = [0] * N
-        for e in hot:
-            w[e] = rng.randint(2, 5)
-        w[rng.randrange(N)] += 1
-        swaps = cache.step(w)
-        assert len(cache.expert_on_gpu) == n and len(set(cache.expert_on_gpu) | set(cache.expert_on_cpu)) == N
-        assert len(swaps) <= 3 and (len(swaps) == 0 or (i + 1) % 4 == 0)
-    assert set(cache.expert_on_gpu) == set(hot)                         # the persistently hot experts end up cached
+    # As printed, u_size experts leave the GPU at every window end, so the hot set stays resident once the cache has
+    # u_size places beyond it (9 places: 6 hot + 3 that rotate).  The guarded variant keeps it with 6 places.
+    for guarded, n in ((False, 9), (True, 6)):
+        cache = sch.WorkloadAwareCache(N, list(range(n)), w_size=4, u_size=3, guarded=guarded)
+        for i in range(64):
+            w = [0] * N
+            for e in hot:
+                w[e] = rng.randint(2, 5)
+            w[rng.randrange(N)] += 1
+            swaps = cache.step(w)
+            assert len(cache.expert_on_gpu) == n and len(set(cache.expert_on_gpu) | set(cache.expert_on_cpu)) == N
+            assert len(swaps) <= 3 and (len(swaps) == 0 or (i + 1) % 4 == 0)
+        assert set(hot) <= set(cache.expert_on_gpu)                     # the persistently hot experts end up cached
+    # with no place to spare the printed policy throws hot experts out again: 3 of the 6 are off the GPU after any window
+    cache = sch.WorkloadAwareCache(N, hot, w_size=4, u_size=3)
+    for i in range(4):
+        cache.step([5 if e in hot else 0 for e in range(N)])
+    assert len(set(hot) - set(cache.expert_on_gpu)) == 3
     # u_size = 0 never swaps; w_size = 1 swaps after every token
     c0 = sch.WorkloadAwareCache(4, [0, 1], 2, 0)
     assert [c0.step([0, 0, 5, 5]) for _ in range(4)] == [[], [], [], []]
