@@ -474,19 +474,26 @@ def main():
         # Workload-Aware Cache Replacement (Alg. 2) replayed over the measured histogram stream, one cache per layer:
         # 64 of 128 experts resident, w_size = 4, u_size = 8; hit rate = share of the routed rows that found their
         # expert resident, against a cache that keeps its initial (lower-half) contents
-        hits = tot = hits_static = loads = 0
+        tot = hits_static = 0
+        hits, loads = {}, {}
         t_sched = time.perf_counter()
+        # Alg. 2 as printed (u_size experts change sides at every window end) and the guarded variant (a pair only while
+        # the incoming score is larger), which is not the paper's
+        for mode_name, mode in (("as_printed", B.CACHE_ALWAYS), ("guarded_variant", B.CACHE_GUARDED)):
+            hits[mode_name] = loads[mode_name] = 0
+            for l in range(args.stack_layers):
+                cache = B.ExpertCache(cfg5.N, range(cfg5.N // 2), 4, 8, mode)
+                for t in range(args.stack_steps):
+                    w = c[t, l]
+                    hits[mode_name] += int(w[cache.on_gpu.astype(bool)].sum())
+                    loads[mode_name] += len(cache.step(w))
+        t_sched = (time.perf_counter() - t_sched) / 2
+        static = np.zeros(cfg5.N, bool)
+        static[: cfg5.N // 2] = True
         for l in range(args.stack_layers):
-            cache = B.ExpertCache(cfg5.N, range(cfg5.N // 2), 4, 8)
-            static = np.zeros(cfg5.N, bool)
-            static[: cfg5.N // 2] = True
             for t in range(args.stack_steps):
-                w = c[t, l]
-                hits += int(w[cache.on_gpu.astype(bool)].sum())
-                hits_static += int(w[static].sum())
-                tot += int(w.sum())
-                loads += len(cache.step(w))
-        t_sched = time.perf_counter() - t_sched
+                hits_static += int(c[t, l][static].sum())
+                tot += int(c[t, l].sum())
         # the comparison policy of Section "Workload-Aware Cache Replacement": least recently used, same capacity and
         # initial contents; an activated expert that is not resident is loaded at once in place of the one unused longest
         hits_lru = loads_lru = 0
@@ -517,8 +524,10 @@ def main():
                "prediction_overlap_us_per_layer": {"eager": {"no_prediction": ov["off"], "inline": ov["inline"], "side_stream": ov["side"], "fused_with_routing": ov["fused"]},
                                                    "graph_replay": {"no_prediction": ovg["off"], "inline": ovg["inline"], "side_stream": ovg["side"], "fused_with_routing": ovg["fused"]}},
                "cache_replacement": {"policy": "workload-aware (Alg. 2), 64 of 128 resident, w_size 4, u_size 8",
-                                     "hit_rate": hits / tot, "hit_rate_static_cache": hits_static / tot,
-                                     "expert_loads_per_layer_step": loads / (args.stack_layers * args.stack_steps),
+                                     "hit_rate": hits["as_printed"] / tot, "hit_rate_static_cache": hits_static / tot,
+                                     "expert_loads_per_layer_step": loads["as_printed"] / (args.stack_layers * args.stack_steps),
+                                     "guarded_variant_hit_rate": hits["guarded_variant"] / tot,
+                                     "guarded_variant_expert_loads_per_layer_step": loads["guarded_variant"] / (args.stack_layers * args.stack_steps),
                                      "lru_hit_rate": hits_lru / tot,
                                      "lru_expert_loads_per_layer_step": loads_lru / (args.stack_layers * args.stack_steps),
                                      "host_us_per_layer_step": t_sched / (args.stack_layers * args.stack_steps) * 1e6},

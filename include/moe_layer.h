@@ -274,12 +274,19 @@ int moe_greedy_assign(int N, const float *t_gpu, const float *t_cpu, uint8_t *G,
  * Workload-Aware Cache Replacement (Alg. 2), one token step of one layer.  score [N] int64 and on_gpu [N] uint8
  * are the persistent state (start with score = 0, *step_in_window = 0 and the initial cache in on_gpu).
  * workload [N] is this step's expert workload (summed over the sequences of the batch).  After every w_size steps
- * the u_size highest-score experts off the GPU replace the u_size lowest-score experts on it -- the text's reading
- * of the algorithm's second TopK -- pairwise, best incoming against worst outgoing, stopping at the first pair
- * whose incoming score is not larger; then the scores are reset.  evicted / loaded [u_size] receive the swapped
- * ids, *n_swapped their number (0 on steps that do not close a window).
+ * the u_size highest-score experts off the GPU replace the u_size lowest-score experts on it (the text's reading
+ * of the algorithm's second TopK; equal scores by ascending index on both sides; min(u_size, experts on, experts off)
+ * when a side has fewer), the i-th evicted paired with the i-th loaded; then the scores are reset.
+ * mode = MOE_CACHE_ALWAYS is the algorithm as printed: the exchange happens whatever the scores are.
+ * mode = MOE_CACHE_GUARDED is a variant that is not in the paper: the pairs are taken in that order only while the
+ * incoming score is larger than the outgoing one.
+ * evicted / loaded [u_size] receive the swapped ids, *n_swapped their number (0 on steps that do not close a window).
+ * Errors: MOE_EINVAL for N outside 1..MOE_MAX_EXPERTS, w_size < 1, u_size < 0, an unknown mode, a NULL pointer
+ * (evicted / loaded may be NULL when u_size = 0).
  */
-int moe_cache_step(int N, int w_size, int u_size, const int32_t *workload, int64_t *score, uint8_t *on_gpu,
+#define MOE_CACHE_ALWAYS  0
+#define MOE_CACHE_GUARDED 1
+int moe_cache_step(int N, int w_size, int u_size, int mode, const int32_t *workload, int64_t *score, uint8_t *on_gpu,
                    int32_t *step_in_window, int32_t *evicted, int32_t *loaded, int32_t *n_swapped);
 
 #ifdef __cplusplus

@@ -237,12 +237,15 @@ def greedy_assign(t_gpu, t_cpu):
     return G, Cc, Tg.value, Tc.value
 
 
+CACHE_ALWAYS, CACHE_GUARDED = 0, 1      # MOE_CACHE_ALWAYS (Alg. 2 as printed), MOE_CACHE_GUARDED (variant)
+
+
 class ExpertCache:
     """Alg. 2 state of one layer, advanced by moe_cache_step."""
 
-    def __init__(self, N: int, on_gpu_ids, w_size: int, u_size: int):
+    def __init__(self, N: int, on_gpu_ids, w_size: int, u_size: int, mode: int = CACHE_ALWAYS):
         import numpy as np
-        self.N, self.w_size, self.u_size = N, w_size, u_size
+        self.N, self.w_size, self.u_size, self.mode = N, w_size, u_size, mode
         self.score = np.zeros(N, np.int64)
         self.on_gpu = np.zeros(N, np.uint8)
         self.on_gpu[list(on_gpu_ids)] = 1
@@ -256,7 +259,7 @@ class ExpertCache:
         n = C.c_int32(0)
         i32, i64, u8 = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
         _check(load_library().moe_cache_step(C.c_int(self.N), C.c_int(self.w_size), C.c_int(self.u_size),
-                                             w.ctypes.data_as(i32), self.score.ctypes.data_as(i64),
+                                             C.c_int(self.mode), w.ctypes.data_as(i32), self.score.ctypes.data_as(i64),
                                              self.on_gpu.ctypes.data_as(u8), C.byref(self.step_in_window),
                                              self._ev.ctypes.data_as(i32), self._ld.ctypes.data_as(i32), C.byref(n)),
                "moe_cache_step")

@@ -59,15 +59,17 @@ int moe_greedy_assign(int N, const float *t_gpu, const float *t_cpu, uint8_t *G,
     return MOE_OK;
 }
 
-// Alg. 2, one token step: score += workload; when the window of w_size steps is complete, swap up to u_size experts:
-// the highest-score experts not on the GPU replace the lowest-score experts on the GPU (a pair is swapped only while the
-// incoming score is larger than the outgoing one), then the scores are reset.  Ties: lower index first.
-int moe_cache_step(int N, int w_size, int u_size, const int32_t *workload, int64_t *score, uint8_t *on_gpu,
+// Alg. 2, one token step: score += workload; when the window of w_size steps is complete, u_size experts change sides:
+// the highest-score experts not on the GPU replace the lowest-score experts on the GPU, then the scores are reset.
+// Ties: lower index first.  MOE_CACHE_GUARDED (a variant, not the paper's) stops at the first pair whose incoming score
+// is not larger than the outgoing one.
+int moe_cache_step(int N, int w_size, int u_size, int mode, const int32_t *workload, int64_t *score, uint8_t *on_gpu,
                    int32_t *step_in_window, int32_t *evicted, int32_t *loaded, int32_t *n_swapped)
 {
     if (N < 1 || N > MOE_MAX_EXPERTS || w_size < 1 || u_size < 0 || !workload || !score || !on_gpu || !step_in_window || !n_swapped)
         return MOE_EINVAL;
     if (u_size > 0 && (!evicted || !loaded)) return MOE_EINVAL;
+    if (mode != MOE_CACHE_ALWAYS && mode != MOE_CACHE_GUARDED) return MOE_EINVAL;
     *n_swapped = 0;
     for (int e = 0; e < N; ++e) score[e] += workload[e];
     *step_in_window += 1;
@@ -79,7 +81,7 @@ int moe_cache_step(int N, int w_size, int u_size, const int32_t *workload, int64
     const int u = std::min(u_size, std::min(nc, ng));
     for (int i = 0; i < u; ++i) {
         const int in = cpu_ids[i], out = gpu_ids[i];
-        if (score[in] <= score[out]) break;                  // no gain from this or any later pair
+        if (mode == MOE_CACHE_GUARDED && score[in] <= score[out]) break;   // no gain from this or any later pair
         on_gpu[out] = 0;
         on_gpu[in] = 1;
         evicted[*n_swapped] = out;

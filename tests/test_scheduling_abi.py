@@ -83,8 +83,9 @@ def test_cache_step_matches_oracle(lib):
         N = rng.choice([8, 60, 128])
         n = rng.randint(1, N - 1)
         w_size, u_size = rng.choice([1, 2, 4, 8]), rng.choice([0, 1, 2, 8])
+        mode = trial % 2                                  # 0: Alg. 2 as printed, 1: the guarded variant
         init = rng.sample(range(N), n)
-        oc = sch.WorkloadAwareCache(N, init, w_size, u_size)
+        oc = sch.WorkloadAwareCache(N, init, w_size, u_size, guarded=bool(mode))
         score = np.zeros(N, np.int64)
         on_gpu = np.zeros(N, np.uint8)
         on_gpu[init] = 1
@@ -101,7 +102,31 @@ def test_cache_step_matches_oracle(lib):
             if i % 13 == 12:
                 hot = rng.sample(range(N), 6)             # the workload shifts
             swaps = oc.step(w.tolist())
-            assert lib.moe_cache_step(N, w_size, u_size, ip(w), lp(score), bp(on_gpu), C.byref(step), ip(ev), ip(ld), C.byref(nsw)) == 0
+            assert lib.moe_cache_step(N, w_size, u_size, mode, ip(w), lp(score), bp(on_gpu), C.byref(step), ip(ev), ip(ld), C.byref(nsw)) == 0
             assert [(int(ev[j]), int(ld[j])) for j in range(nsw.value)] == swaps
             assert np.nonzero(on_gpu)[0].tolist() == oc.expert_on_gpu
             assert score.tolist() == oc.s and step.value == oc.i % w_size
+
+
+def test_cache_step_hand_trace_and_errors(lib):
+    """The golden window-2 exchange through the C ABI under both modes, and the argument checks."""
+    steps = [[0, 1, 0, 0, 3, 0, 2, 0], [1, 0, 0, 0, 2, 0, 2, 1], [0, 0, 1, 0, 3, 1, 1, 0], [0, 1, 0, 0, 2, 0, 3, 0]] + [[0, 0, 0, 0, 2, 0, 2, 0]] * 4
+    for mode, want2, after2 in ((0, [(1, 0), (2, 3)], [0, 3, 4, 6]), (1, [], [1, 2, 4, 6])):
+        score, on_gpu = np.zeros(8, np.int64), np.array([1, 1, 1, 1, 0, 0, 0, 0], np.uint8)
+        step, nsw = C.c_int32(0), C.c_int32(0)
+        ev, ld = np.full(2, -1, np.int32), np.full(2, -1, np.int32)
+        got = []
+        for w in steps:
+            wa = np.array(w, np.int32)
+            assert lib.moe_cache_step(8, 4, 2, mode, ip(wa), lp(score), bp(on_gpu), C.byref(step), ip(ev), ip(ld), C.byref(nsw)) == 0
+            got.append([(int(ev[j]), int(ld[j])) for j in range(nsw.value)])
+        assert got[3] == [(3, 4), (0, 6)] and got[7] == want2
+        assert [g for i, g in enumerate(got) if i not in (3, 7)] == [[]] * 6
+        assert np.nonzero(on_gpu)[0].tolist() == after2
+    wa, score, on_gpu = np.zeros(8, np.int32), np.zeros(8, np.int64), np.zeros(8, np.uint8)
+    step, nsw = C.c_int32(0), C.c_int32(0)
+    ev = np.zeros(2, np.int32)
+    args = (ip(wa), lp(score), bp(on_gpu), C.byref(step), ip(ev), ip(ev), C.byref(nsw))
+    assert lib.moe_cache_step(8, 4, 2, 2, *args) == -1            # unknown mode
+    assert lib.moe_cache_step(8, 0, 2, 0, *args) == -1
+    assert lib.moe_cache_step(129, 4, 2, 0, *args) == -1
