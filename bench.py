@@ -455,7 +455,7 @@ def main():
         return
 
     if args.stack:
-        from paper_2602_03495_amd.stack import DecodeStack
+        from bench_stack import DecodeStack
         cfg5 = wl.CONFIGS["qwen3"]
         t0 = time.time()
         st = DecodeStack(cfg5, args.stack_layers, 16)

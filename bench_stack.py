@@ -1,12 +1,14 @@
-"""Decode run over a stack of MoE layers with temporally correlated routing (the Qwen3-30B-A3B-shaped workload):
-every step feeds a fresh batch through all layers, each layer's gate bias follows an AR(1) path around its Zipf
-mean, the expert mask of a layer is the top half of that layer's previous-step workloads, and the next layer's
-workload is predicted from the current features plus a calibrated residual vector.
+"""Measurement harness beside bench.py (not part of the library package): a decode run over a stack of MoE layers with
+temporally correlated routing (the Qwen3-30B-A3B-shaped workload).  Every step feeds a fresh batch through all layers,
+each layer's gate bias follows an AR(1) path around its Zipf mean, the expert mask of a layer is the top half of that
+layer's previous-step workloads, and the next layer's workload is predicted from the current features plus a
+calibrated residual vector.
 
-Plumbing only: the layer arithmetic runs in the library's kernels; the glue between layers -- the residual
-connection followed by an RMS normalisation, h <- rmsnorm(h + MoE(h)), which keeps the synthetic stream at unit
-scale over 48 layers the way a transformer block's norm does -- and the bookkeeping of histograms are done with
-torch tensor ops, outside the timed calls.
+The layer arithmetic runs in the library's kernels.  What stands in for the rest of a transformer block between two MoE
+layers is harness code, done with torch tensor ops outside the timed calls: the residual connection followed by an RMS
+normalisation, h <- rmsnorm(h + MoE(h)).  The normalisation is this harness's choice (the paper's prefetching section
+relies on the residual connection only): it keeps the synthetic stream at unit scale over 48 layers the way a block's
+norm layers do, so that every layer's gate sees inputs of the scale its weights were drawn for.
 """
 from __future__ import annotations
 
@@ -16,9 +18,9 @@ from typing import List, Optional
 import numpy as np
 import torch
 
-from . import binding as B
-from . import layer as Lm
-from . import workloads as wl
+from paper_2602_03495_amd import binding as B
+from paper_2602_03495_amd import layer as Lm
+from paper_2602_03495_amd import workloads as wl
 
 
 @dataclass
@@ -28,6 +30,7 @@ class StackResult:
     seconds: float                # GPU time of the timed calls (route + predict + ffn + combine), all steps
     tokens_per_s: float
     acc: dict = field(default_factory=dict)   # p -> mean |pred_top_p & true_top_p| / p (tie tolerant)
+    io: list = field(default_factory=list)    # keep_io: per (step, layer) the layer's input, mask, bias, tables and output, on the host
 
 
 def next_hidden(h: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
@@ -77,7 +80,7 @@ class DecodeStack:
             self.res_vec[l] = cal[l].finish()
 
     def run(self, steps: int, bias: torch.Tensor, use_res_vec: bool = True, p_list=(1, 4, 8),
-            predict: str = "fused") -> StackResult:
+            predict: str = "fused", keep_io: bool = False) -> StackResult:
         """predict: "fused" routes and predicts with one call (moe_route_predict); "inline" issues the prediction between routing and the expert FFN on the same stream; "side"
         issues it on a second stream of the same priority, concurrent with routing, FFN and combine, and joins it
         before the layer ends (the separate work stream of the paper's system overview); "off" skips it."""
@@ -91,6 +94,7 @@ class DecodeStack:
         zero_rv = torch.zeros(cfg.d, dtype=torch.float32, device="cuda")
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         total_ms = 0.0
+        io = []
         for t in range(steps):
             h = Lm.to_device_bf16(wl.hidden_states(cfg, self.T, draw=t))
             for l in range(nl):
@@ -118,6 +122,14 @@ class DecodeStack:
                 e1.synchronize()
                 total_ms += e0.elapsed_time(e1)
                 counts[t, l] = L.routing.counts
+                if keep_io:       # what a checker needs to recompute this layer pass from the input the GPU really saw
+                    r = L.routing
+                    io.append({"step": t, "layer": l, "h": Lm.from_device_bf16(h), "mask": masks[l].cpu().numpy(),
+                               "bias": b.cpu().numpy(), "topk_idx": r.topk_idx.cpu().numpy(), "topk_w": r.topk_w.cpu().numpy(),
+                               "counts": r.counts.cpu().numpy(), "offsets": r.offsets.cpu().numpy(), "perm": r.perm.cpu().numpy(),
+                               "inv_perm": r.inv_perm.cpu().numpy(), "out": Lm.from_device_bf16(out),
+                               "pred_counts": L.pred_counts.cpu().numpy() if do_pred else None,
+                               "res_vec": rv.cpu().numpy(), "next_bias": None if nb is None else nb.cpu().numpy()})
                 if do_pred:
                     preds[t, l] = L.pred_counts
                 # next step's mask of this layer: the half of the experts with the largest workloads now
@@ -128,7 +140,7 @@ class DecodeStack:
                 masks[l] = m
                 h = next_hidden(h, out)
         c, pr = counts.cpu().numpy(), preds.cpu().numpy()
-        res = StackResult(c, pr, total_ms * 1e-3, self.T * steps / (total_ms * 1e-3))
+        res = StackResult(c, pr, total_ms * 1e-3, self.T * steps / (total_ms * 1e-3), io=io)
         for p in p_list:
             if nl > 1 and predict != "off":
                 res.acc[p] = float(np.mean([top_p_accuracy(pr[t, l], c[t, l + 1], p) for t in range(steps) for l in range(nl - 1)]))

@@ -107,3 +107,54 @@ def sample_tokens(T: int, n: int, seed: int, extra=()) -> np.ndarray:
     rng = np.random.default_rng(seed)
     s = set(rng.choice(T, size=min(n, T), replace=False).tolist()) | set(int(x) for x in extra)
     return np.array(sorted(s), dtype=np.int32)
+
+
+SENTINEL = 0x5A5A      # bf16 bits of a large finite value (1.5e16): a row that was not written still holds it
+
+
+def run_layer(B, Lm, cfg, T, masks, ffn_path, draw=0):
+    """One layer pass per mask through the library, compared with the oracle on the same bits: routing tables, every
+    expert row of the masked-on experts, the layer output; rows of masked-off experts must be left untouched."""
+    import torch
+    _np = lambda t: t.cpu().numpy()
+    hl = make_host_layer(cfg)
+    h = wl.hidden_states(cfg, T, draw=draw)
+    lg, o_idx, o_w, o_counts = oracle.route(h, hl.gate_w, hl.bias, cfg.k, cfg.norm_mode)
+    dw = Lm.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2, hl.shared)
+    L = Lm.MoeLayer(cfg, T, ffn_path)
+    hd = Lm.to_device_bf16(h)
+    for mask in masks:
+        md = None if mask is None else torch.from_numpy(mask).cuda()
+        L.y.view(torch.int16).fill_(SENTINEL)
+        out = L.forward(hd, dw, md)
+        torch.cuda.synchronize()
+        r = L.routing
+        ex = check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
+                           _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
+        keep = np.nonzero(~ex)[0].astype(np.int32)
+        # expert rows, in the oracle's (token, slot) order
+        y_ref = oracle.expert_rows(h, o_idx, hl.w1, hl.w3, hl.w2, mask, tokens=keep)
+        y_bits = Lm.from_device_bf16(L.y)
+        y_gpu = wl.bf16_bits_to_f32(y_bits)
+        g_idx, inv = _np(r.topk_idx), _np(r.inv_perm).reshape(T, cfg.k)
+        on = np.ones(cfg.N, bool) if mask is None else mask.astype(bool)
+        for n, t in enumerate(keep):
+            for s_o in range(cfg.k):
+                e = o_idx[t, s_o]
+                if not on[e]:
+                    continue
+                s_g = int(np.nonzero(g_idx[t] == e)[0][0])
+                err = rel_err(y_gpu[inv[t, s_g]], y_ref[n, s_o])
+                assert err <= OUT_TOL, (t, e, err)
+        # rows of masked-off experts are not written (they keep the sentinel); rows of masked-on experts all are
+        off_rows = ~on[np.sort(g_idx.ravel(), kind="stable")]          # permuted row p belongs to the p-th smallest expert id
+        assert np.all(y_bits[off_rows] == SENTINEL), "a row of a masked-off expert was written"
+        assert not np.any(np.all(y_bits[~off_rows] == SENTINEL, axis=1)), "a row of a masked-on expert was not written"
+        # layer output
+        ref = oracle.layer(h, o_idx, o_w, hl.w1, hl.w3, hl.w2, mask, hl.shared, hl.shared_mode, tokens=keep)
+        got = wl.bf16_bits_to_f32(Lm.from_device_bf16(out))[keep]
+        if np.abs(ref).max() == 0:
+            assert np.all(got == 0)
+        else:
+            assert rel_err(got, ref) <= OUT_TOL, rel_err(got, ref)
+    return L

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from paper_2602_03495_amd import workloads as wl
-from helpers import OUT_TOL, check_routing, make_host_layer, rel_err
+from helpers import OUT_TOL, check_routing, make_host_layer, rel_err, run_layer
 
 pytestmark = pytest.mark.gpu
 
@@ -90,43 +90,7 @@ def test_route_extreme_bias_sends_every_token_to_one_expert(gpu):
 
 
 # ------------------------------------------------------------------------------------------- expert FFN + combine
-def _run_layer(B, Lm, cfg, T, masks, ffn_path, draw=0):
-    hl = make_host_layer(cfg)
-    h = wl.hidden_states(cfg, T, draw=draw)
-    lg, o_idx, o_w, o_counts = oracle.route(h, hl.gate_w, hl.bias, cfg.k, cfg.norm_mode)
-    dw = _upload(Lm, hl)
-    L = Lm.MoeLayer(cfg, T, ffn_path)
-    hd = Lm.to_device_bf16(h)
-    for mask in masks:
-        md = None if mask is None else torch.from_numpy(mask).cuda()
-        L.y.zero_()
-        out = L.forward(hd, dw, md)
-        torch.cuda.synchronize()
-        r = L.routing
-        ex = check_routing(lg, o_idx, o_w, o_counts, _np(r.topk_idx), _np(r.topk_w), _np(r.counts), _np(r.offsets),
-                           _np(r.perm), _np(r.inv_perm), cfg.N, cfg.k)
-        keep = np.nonzero(~ex)[0].astype(np.int32)
-        # expert rows, in the oracle's (token, slot) order
-        y_ref = oracle.expert_rows(h, o_idx, hl.w1, hl.w3, hl.w2, mask, tokens=keep)
-        y_gpu = wl.bf16_bits_to_f32(Lm.from_device_bf16(L.y))
-        g_idx, inv = _np(r.topk_idx), _np(r.inv_perm).reshape(T, cfg.k)
-        on = np.ones(cfg.N, bool) if mask is None else mask.astype(bool)
-        for n, t in enumerate(keep):
-            for s_o in range(cfg.k):
-                e = o_idx[t, s_o]
-                if not on[e]:
-                    continue
-                s_g = int(np.nonzero(g_idx[t] == e)[0][0])
-                err = rel_err(y_gpu[inv[t, s_g]], y_ref[n, s_o])
-                assert err <= OUT_TOL, (t, e, err)
-        # layer output
-        ref = oracle.layer(h, o_idx, o_w, hl.w1, hl.w3, hl.w2, mask, hl.shared, hl.shared_mode, tokens=keep)
-        got = wl.bf16_bits_to_f32(Lm.from_device_bf16(out))[keep]
-        if np.abs(ref).max() == 0:
-            assert np.all(got == 0)
-        else:
-            assert rel_err(got, ref) <= OUT_TOL, rel_err(got, ref)
-    return L
+_run_layer = run_layer
 
 
 @pytest.mark.parametrize("path", ["tiled", "skinny"])
