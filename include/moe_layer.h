@@ -38,6 +38,7 @@ extern "C" {
 #define MOE_EUNSUPPORTED -2   /* a valid request this build has no kernel for */
 #define MOE_ELAUNCH      -3   /* the HIP runtime refused a launch (hipGetLastError) */
 #define MOE_EWORKSPACE   -4   /* workspace pointer not 256-byte aligned */
+#define MOE_ETOOLARGE    -5   /* moe_expert_ffn_static: the shape needs more scratch than the static array holds */
 
 #define MOE_MAX_EXPERTS 128
 #define MOE_MAX_TOPK      8
@@ -169,6 +170,26 @@ int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const
 int moe_expert_ffn_stage(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const void *w1, const void *w3, const void *w2,
                          const uint8_t *expert_mask, void *y, void *workspace, int stages, void *stream);
+
+/*
+ * moe_expert_ffn for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but
+ * the scratch (inner activations, split-K partial sums, tile tables) lives in an array that is part of the library's
+ * code object: moe_static_scratch_bytes() bytes (32 MiB) on every GPU the library runs on, held until the process ends.
+ * The call allocates and frees nothing.
+ *   - Shapes whose moe_workspace_bytes() exceeds moe_static_scratch_bytes() are rejected with MOE_ETOOLARGE before
+ *     anything is launched (all decode shapes fit: T <= 16 needs at most 3.7 MB + 8.4 MB at d = 4096, I = 14336;
+ *     prefill shapes fit while T*k*I*2 bytes of activations do).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ *     threads) race; calls in stream order do not.  Nothing in the array has to start at zero: every call builds its
+ *     own tile tables and writes each activation and partial sum before reading it.
+ *   - The array's device address is looked up on the first call on each device (hipGetSymbolAddress, no allocation);
+ *     the device that is current at the call must be the one that owns the other buffers.
+ */
+size_t moe_static_scratch_bytes(void);
+int moe_expert_ffn_static(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets,
+                          const int32_t *counts, const void *w1, const void *w3, const void *w2,
+                          const uint8_t *expert_mask, void *y, void *stream);
 
 /*
  * Weighted combine (Eq. 2, restricted to the experts with G_i = 1):

@@ -19,7 +19,8 @@ MAX_EXPERTS, MAX_TOPK = 128, 8        # MOE_MAX_EXPERTS, MOE_MAX_TOPK of include
 EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_workload", "moe_expert_ffn",
            "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
            "moe_expert_times", "moe_greedy_assign", "moe_cache_step", "moe_res_vec_workspace_bytes",
-           "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict", "moe_append_shared"]
+           "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict", "moe_append_shared",
+           "moe_expert_ffn_static", "moe_static_scratch_bytes"]
 
 
 class MoeShape(C.Structure):
@@ -46,6 +47,7 @@ def load_library():
         for name in EXPORTS[1:]:
             getattr(_lib, name).restype = C.c_int
         _lib.moe_res_vec_workspace_bytes.restype = C.c_size_t
+        _lib.moe_static_scratch_bytes.restype = C.c_size_t
     return _lib
 
 
@@ -172,6 +174,20 @@ def moe_expert_ffn(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mas
                                        _ptr(y, torch.bfloat16), _ws_ptr(ws), _stream())
     _check(rc, "moe_expert_ffn")
     return y
+
+
+def moe_expert_ffn_static(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, expert_mask, y):
+    """moe_expert_ffn on the library's static scratch array (no workspace argument, no allocation)."""
+    rc = load_library().moe_expert_ffn_static(C.byref(s), _ptr(h, torch.bfloat16), _ptr(perm, torch.int32),
+                                              _ptr(offsets, torch.int32), _ptr(counts, torch.int32), _ptr(w1, torch.bfloat16),
+                                              _ptr(w3, torch.bfloat16), _ptr(w2, torch.bfloat16), _ptr(expert_mask, torch.uint8),
+                                              _ptr(y, torch.bfloat16), _stream())
+    _check(rc, "moe_expert_ffn_static")
+    return y
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().moe_static_scratch_bytes())
 
 
 STAGE_UP, STAGE_DOWN, STAGE_ALL = 1, 2, 3

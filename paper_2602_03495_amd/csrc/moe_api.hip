@@ -1,6 +1,8 @@
 // extern "C" boundary of the library: argument validation on the host, then the kernel launchers.
 #include "moe_common.h"
 
+#include <mutex>
+
 int moe_route_impl(const moe_shape *, const void *, const void *, const float *, int, int32_t *, float *, int32_t *,
                    int32_t *, int32_t *, int32_t *, void *, hipStream_t);
 int moe_predict_impl(const moe_shape *, const void *, const float *, const void *, const float *, int, int32_t *,
@@ -27,6 +29,30 @@ int moe_res_vec_finish_impl(int, const double *, long long, float *, hipStream_t
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
+// ---- scratch of the entry point that allocates nothing -----------------------------------------------------------
+// One array per GPU, part of the loaded code object, held until the process ends.  In host code the array's name is
+// only a handle: its device address is looked up once per device and that address is what the kernels receive.
+#define MOE_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+#define MOE_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char moe_static_scratch[MOE_STATIC_SCRATCH_BYTES];
+static void *g_scratch_ptr[MOE_MAX_DEVICES];      // device address of the current device's copy, looked up on first use
+static std::mutex g_scratch_lock;
+
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MOE_MAX_DEVICES) return MOE_ELAUNCH;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(moe_static_scratch)) != hipSuccess || p == nullptr) return MOE_ELAUNCH;
+        if (((uintptr_t)p & 255u) != 0) return MOE_EWORKSPACE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+
 // sizes every entry point relies on
 static int check_shape(const moe_shape *s, bool need_I)
 {
@@ -49,6 +75,7 @@ const char *moe_strerror(int code)
     case MOE_EUNSUPPORTED: return "request not supported by this build (shape outside the chosen FFN path)";
     case MOE_ELAUNCH: return "HIP kernel launch failed";
     case MOE_EWORKSPACE: return "workspace pointer must be 256-byte aligned";
+    case MOE_ETOOLARGE: return "shape needs more scratch than the library's static scratch array holds (see moe_static_scratch_bytes)";
     default: return "unknown error code";
     }
 }
@@ -118,6 +145,20 @@ int moe_expert_ffn(const moe_shape *s, const void *h, const int32_t *perm, const
                    void *stream)
 {
     return moe_expert_ffn_stage(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, workspace, MOE_FFN_STAGE_ALL, stream);
+}
+
+size_t moe_static_scratch_bytes(void) { return MOE_STATIC_SCRATCH_BYTES; }
+
+int moe_expert_ffn_static(const moe_shape *s, const void *h, const int32_t *perm, const int32_t *offsets, const int32_t *counts,
+                          const void *w1, const void *w3, const void *w2, const uint8_t *expert_mask, void *y, void *stream)
+{
+    int rc = check_shape(s, true);
+    if (rc != MOE_OK) return rc;
+    if (moe_ws(s).total > MOE_STATIC_SCRATCH_BYTES) return MOE_ETOOLARGE;
+    void *scratch = nullptr;
+    rc = static_scratch(&scratch);
+    if (rc != MOE_OK) return rc;
+    return moe_expert_ffn_stage(s, h, perm, offsets, counts, w1, w3, w2, expert_mask, y, scratch, MOE_FFN_STAGE_ALL, stream);
 }
 
 int moe_combine(const moe_shape *s, const void *y, const int32_t *topk_idx, const float *topk_w, const int32_t *inv_perm,
