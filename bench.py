@@ -27,9 +27,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # flop/s, MI355X dense bf16 matrix peak
 PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
-# HBM bytes per launch of the dominant kernels (fetched + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# of this script, scaled by what the same counters read for a plain 1 GiB copy (see profiles/)
-TRAFFIC_PREFILL_UP = 2.023e9 + 87.3e6
+# HBM bytes per launch of the dominant kernels (fetched + written).  STORED counter values, not measured by the run that
+# prints them: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for a
+# plain 1 GiB copy; the profile they come from is named beside them in the JSON line.
+TRAFFIC_SOURCE = "stored counter value from profiles/traffic_mixtral_hbm_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), not measured in this run"
+TRAFFIC_PREFILL = {"up": 2.023e9 + 87.3e6, "down": 1.063e9 + 24.9e6}
 TRAFFIC_DECODE_UP = {1: 470.0e6, 16: 1.175e9 + 0.75e6}
 
 
@@ -38,34 +40,40 @@ def log(*a):
 
 
 def time_steps(torch, B, L, hd, dw, mask_d, steps, warmup):
-    """Run warmup + steps passes; returns (wall seconds for the timed steps, mean seconds of the up-projection
-    stage, mean seconds of the whole FFN), with HIP events recorded on the stream the kernels run on."""
+    """Run warmup + steps passes.  Returns a dict of seconds: wall (all timed steps, host clock around two
+    synchronisations), and mean / median over the timed steps of the whole step, the up-projection stage, the
+    down-projection stage and the whole expert FFN, from HIP events recorded on the stream the kernels run on."""
     r, s = L.routing, L.shape
 
     def one(ev=None):
-        L.route(hd, dw)
         if ev is not None:
             ev[0].record()
-        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_UP)
+        L.route(hd, dw)
         if ev is not None:
             ev[1].record()
-        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_DOWN)
+        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_UP)
         if ev is not None:
             ev[2].record()
+        B.moe_expert_ffn_stage(s, hd, r.perm, r.offsets, r.counts, dw.w1, dw.w3, dw.w2, mask_d, L.y, L.ws, B.STAGE_DOWN)
+        if ev is not None:
+            ev[3].record()
         L.combine(mask_d)
+        if ev is not None:
+            ev[4].record()
 
     for _ in range(warmup):
         one()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
         one(evs[i])
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    up = sum(e[0].elapsed_time(e[1]) for e in evs) / steps * 1e-3
-    ffn = sum(e[0].elapsed_time(e[2]) for e in evs) / steps * 1e-3
-    return wall, up, ffn
+    out = {"wall": time.perf_counter() - t0}
+    for name, a, b in (("step", 0, 4), ("up", 1, 2), ("down", 2, 3), ("ffn", 1, 3)):
+        ts = sorted(e[a].elapsed_time(e[b]) * 1e-3 for e in evs)
+        out[name + "_mean"], out[name + "_median"] = sum(ts) / steps, ts[steps // 2]
+    return out
 
 
 def median_event_seconds(torch, fn, runs=20, flush=None):
@@ -249,8 +257,8 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
             step(evs[i])
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / steps
-        ffn = sum(e[0].elapsed_time(e[1]) for e in evs) / steps * 1e-3
-        sh = sum(e[1].elapsed_time(e[2]) for e in evs) / steps * 1e-3
+        med = lambda a, b: sorted(e[a].elapsed_time(e[b]) for e in evs)[steps // 2] * 1e-3
+        ffn, sh = med(0, 1), med(1, 2)
         rows_on, active = int(counts[on].sum()), int(((counts > 0) & on).sum())
         if T <= 16:
             # a decode step touches few hundred MB at most: flush the Infinity Cache between steps so that it is HBM traffic
@@ -260,10 +268,18 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
             ffn = median_event_seconds(torch, lambda: L.expert_ffn(hd, dw, md), steps, flush)
             if cfg.n_shared:
                 sh = median_event_seconds(torch, lambda: L.shared_ffn(hd, dw), steps, flush)
+        # both bounds of the routed FFN (algorithmic flops of the masked-on routed rows; weights of the touched masked-on
+        # experts once from HBM) and of the layer's whole expert work, shared experts included (always on: T rows each)
+        F_r, B_r = 6.0 * cfg.d * cfg.I * rows_on, 6.0 * cfg.d * cfg.I * active
+        F_s, B_s = 6.0 * cfg.d * cfg.I_shared * cfg.n_shared * T, 6.0 * cfg.d * cfg.I_shared * cfg.n_shared
+        t_all = ffn + (sh if cfg.n_shared else 0.0)
         rec = {"workload": name, "tokens": T, "mask": mask_kind, "us_per_step": wall * 1e6, "tokens_per_s": T / wall,
-               "ffn_us": ffn * 1e6, "ffn_mfma_frac": 6.0 * cfg.d * cfg.I * rows_on / ffn / PEAK_BF16_MFMA,
-               "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * active / ffn / PEAK_HBM, "shared_us": sh * 1e6 if cfg.n_shared else 0.0,
+               "ffn_us": ffn * 1e6, "ffn_mfma_frac": F_r / ffn / PEAK_BF16_MFMA,
+               "ffn_hbm_frac": B_r / ffn / PEAK_HBM, "shared_us": sh * 1e6 if cfg.n_shared else 0.0,
+               "experts_mfma_frac": (F_r + F_s) / t_all / PEAK_BF16_MFMA, "experts_hbm_frac": (B_r + B_s) / t_all / PEAK_HBM,
                "active_experts": active, "rows_on": rows_on}
+        rec["bound"] = "mfma" if rec["experts_mfma_frac"] >= rec["experts_hbm_frac"] else "hbm"
+        rec["bound_frac"] = max(rec["experts_mfma_frac"], rec["experts_hbm_frac"])     # max(F / (t P_mfma), B / (t BW))
         if L.n_merged:
             # the same layer with its shared experts inside the grouped launches (moe_append_shared)
             xm = L.merged_mask(md)
@@ -393,12 +409,17 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=50)
     ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens of the prefill batch the oracle is timed on (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the DeepSeek-V2-Lite-, Qwen1.5-MoE- and Qwen3-shaped layers")
     ap.add_argument("--stack", action="store_true",
                     help="run the Qwen3-30B-A3B-shaped decode stack instead (48 layers, 256 steps, batch 16, AR(1) routing) "
                          "and print its own JSON line: per-step workload histograms, prediction accuracy, tokens/s")
     ap.add_argument("--survey", action="store_true",
                     help="time the other layer shapes instead (DeepSeek-V2-Lite, Qwen1.5-MoE, Qwen3-30B-A3B and Mixtral; prefill, "
                          "decode and the mid-sized batches between them) and print one JSON line with all records")
+    ap.add_argument("--one", default=None, metavar="SHAPE:TOKENS:MASK",
+                    help="time one layer shape at one batch size instead, e.g. deepseek:2048:half, qwen15:1:all, mixtral:2048:rand6 "
+                         "(mask: all | half = top half by this batch's workloads | rand6); prints one JSON record; the run to "
+                         "profile when per-shape kernel statistics or counters are wanted")
     ap.add_argument("--stack-layers", type=int, default=48)
     ap.add_argument("--stack-steps", type=int, default=256)
     ap.add_argument("--assign", action="store_true",
@@ -438,6 +459,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log("[bench] calibration copy done: 5 x (1 GiB read + 1 GiB written)")
+        return
+
+    if args.one:
+        name, T1, mk = args.one.split(":")
+        rec = survey_config(torch, B, Lm, wl, name, [int(T1)], mk, steps=args.steps)[0]
+        print(json.dumps({"metric": "MoE-layer step time, one shape", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{name}-shaped layer, {T1} tokens, mask {mk}"}, **rec}), flush=True)
         return
 
     if args.survey:
@@ -550,22 +578,36 @@ def main():
     h = wl.hidden_states(cfg, T)
     hd = Lm.to_device_bf16(h)
     L = Lm.MoeLayer(cfg, T)
-    wall, up, ffn = time_steps(torch, B, L, hd, dw, mask_d, args.steps, args.warmup)
+    t = time_steps(torch, B, L, hd, dw, mask_d, args.steps, args.warmup)
     counts = L.routing.counts.cpu().numpy()
     rows_on = int(counts[on].sum())
+    active = int(((counts > 0) & on).sum())
     up_flops = 4.0 * cfg.d * cfg.I * rows_on           # gate + up products of the masked-on rows
-    ffn_flops = 6.0 * cfg.d * cfg.I * rows_on
-    ms_per_step = wall / args.steps * 1e3
-    value = T / (wall / args.steps)
-    log(f"[bench] prefill T={T}: {ms_per_step:.3f} ms/step, up {up * 1e3:.3f} ms, ffn {ffn * 1e3:.3f} ms, "
-        f"counts={counts.tolist()}, rows_on={rows_on}")
-    roofline = {"bound": "mfma", "kernel": "ffn_tiled_kernel<0,4,8> (gate/up projection + SwiGLU)",
-                "achieved": up_flops / up / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
-                "frac": up_flops / up / PEAK_BF16_MFMA, "traffic": TRAFFIC_PREFILL_UP,
-                "ffn_achieved": ffn_flops / ffn / 1e12, "ffn_frac": ffn_flops / ffn / PEAK_BF16_MFMA,
-                "flops_per_launch": up_flops, "avg_launch_ms": up * 1e3,
-                # the other bound of the same FFN: weights of the touched masked-on experts once from HBM
-                "ffn_hbm_frac": 6.0 * cfg.d * cfg.I * int(((counts > 0) & on).sum()) / ffn / PEAK_HBM}
+    down_flops = 2.0 * cfg.d * cfg.I * rows_on
+    ffn_flops = up_flops + down_flops                   # 6 d I per masked-on routed row
+    ffn_bytes = 6.0 * cfg.d * cfg.I * active            # the other bound: weights of the touched masked-on experts once
+    ms_per_step = t["wall"] / args.steps * 1e3
+    value = T / (t["wall"] / args.steps)
+    log(f"[bench] prefill T={T}: {ms_per_step:.3f} ms/step (median {t['step_median'] * 1e3:.3f}), up {t['up_mean'] * 1e3:.3f} ms, "
+        f"down {t['down_mean'] * 1e3:.3f} ms, ffn {t['ffn_mean'] * 1e3:.3f} ms, counts={counts.tolist()}, rows_on={rows_on}")
+    frac = lambda fl, sec: fl / sec / PEAK_BF16_MFMA
+    # The dominant work is the expert FFN: two launches (up projection + SwiGLU, down projection).  achieved = its
+    # algorithmic flops, 6 d I per masked-on routed row, over the mean time of the two launches per step.
+    roofline = {"bound": "mfma", "kernel": "expert FFN: ffn_tiled_kernel<0,...> (gate/up projection + SwiGLU) + ffn_tiled_kernel<1,...> (down projection)",
+                "achieved": ffn_flops / t["ffn_mean"] / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
+                "frac": frac(ffn_flops, t["ffn_mean"]), "traffic": TRAFFIC_PREFILL["up"] + TRAFFIC_PREFILL["down"],
+                "traffic_source": TRAFFIC_SOURCE,
+                "flops_per_launch": ffn_flops, "avg_launch_ms": t["ffn_mean"] * 1e3, "median_launch_ms": t["ffn_median"] * 1e3,
+                "frac_of_median": frac(ffn_flops, t["ffn_median"]),
+                "per_kernel": {
+                    "up": {"flops_per_launch": up_flops, "avg_launch_ms": t["up_mean"] * 1e3, "median_launch_ms": t["up_median"] * 1e3,
+                           "frac": frac(up_flops, t["up_mean"]), "traffic": TRAFFIC_PREFILL["up"]},
+                    "down": {"flops_per_launch": down_flops, "avg_launch_ms": t["down_mean"] * 1e3, "median_launch_ms": t["down_median"] * 1e3,
+                             "frac": frac(down_flops, t["down_mean"]), "traffic": TRAFFIC_PREFILL["down"]}},
+                "ffn_frac": frac(ffn_flops, t["ffn_mean"]),
+                # the other bound of the same FFN, and the larger of the two (what a perfect kernel would be held to)
+                "ffn_hbm_frac": ffn_bytes / t["ffn_mean"] / PEAK_HBM,
+                "bound_frac": max(frac(ffn_flops, t["ffn_mean"]), ffn_bytes / t["ffn_mean"] / PEAK_HBM)}
     # the next-layer workload prediction is not part of the step above; alone it costs (next gate = this layer's, a stand-in)
     rv = torch.from_numpy(wl.layer_drift(cfg)).cuda()
     top = torch.empty(1, dtype=torch.int32, device="cuda")
@@ -577,7 +619,8 @@ def main():
         for Td in (1, 16):
             hdd = Lm.to_device_bf16(wl.hidden_states(cfg, Td, draw=10 + Td))
             Ld = Lm.MoeLayer(cfg, Td)
-            wall_d, up_d, ffn_d = time_steps(torch, B, Ld, hdd, dw, mask_d, args.decode_steps, args.warmup)
+            td = time_steps(torch, B, Ld, hdd, dw, mask_d, args.decode_steps, args.warmup)
+            wall_d, up_d, ffn_d = td["wall"], td["up_mean"], td["ffn_mean"]
             c = Ld.routing.counts.cpu().numpy()
             active = int(((c > 0) & on).sum())
             up_bytes = 4.0 * cfg.d * cfg.I * active          # W1 and W3 of the touched, masked-on experts, bf16
@@ -590,7 +633,8 @@ def main():
                                         "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": up_bytes / up_d / PEAK_HBM if active else 0.0,
                                         "ffn_frac": ffn_bytes / ffn_d / PEAK_HBM if active else 0.0,
                                         "step_frac": ffn_bytes / (wall_g / args.decode_steps) / PEAK_HBM if active else 0.0,
-                                        "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "traffic": TRAFFIC_DECODE_UP.get(Td)}})
+                                        "bytes_per_launch": up_bytes, "avg_launch_ms": up_d * 1e3, "median_launch_ms": td["up_median"] * 1e3,
+                                        "traffic": TRAFFIC_DECODE_UP.get(Td), "traffic_source": TRAFFIC_SOURCE}})
             predict_us[f"decode_{Td}"] = median_event_seconds(torch, lambda: Ld.predict(hdd, rv, dw, 1, top)) * 1e6
             predict_us[f"decode_{Td}_route_alone"] = median_event_seconds(torch, lambda: Ld.route(hdd, dw)) * 1e6
             predict_us[f"decode_{Td}_route_and_predict_fused"] = median_event_seconds(
@@ -612,12 +656,23 @@ def main():
                "sample": f"first {n} tokens of the prefill batch, route + masked expert FFN + combine, {dt:.1f} s"}
         log(f"[bench] oracle: {n} tokens in {dt:.1f}s on {cpu['cores']} threads")
 
+    # ---- the other layer shapes, same run (prefill and decode of each; eager launches, HIP events between the calls,
+    # medians; decode steps with the Infinity Cache read through between steps) --------------------------------------
+    others = []
+    if not args.no_other_workloads:
+        del dw, L
+        torch.cuda.empty_cache()
+        for name, Ts, mk in (("deepseek", [2048, 16], "half"), ("qwen15", [4096, 1], "all"), ("qwen3", [2048, 16], "half")):
+            others += survey_config(torch, B, Lm, wl, name, Ts, mk)
+
     out = {"metric": "MoE-layer tokens/sec (prefill 2048 tok)", "value": value, "unit": "tokens/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "median_ms_per_step": t["step_median"] * 1e3,
+           "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "mixtral-8x7b-shaped layer, prefill 2048 tokens", "d": cfg.d, "experts": cfg.N,
                       "top_k": cfg.k, "inner": cfg.I, "experts_on_gpu": int(on.sum()), "tokens": T},
-           "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "predict_workload_us": predict_us}
+           "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "predict_workload_us": predict_us,
+           "other_workloads": others}
     print(json.dumps(out), flush=True)
 
 
