@@ -52,13 +52,21 @@ extern "C" {
 #define MOE_FFN_TILED  1      /* LDS-tiled bf16 MFMA grouped GEMMs (prefill) */
 #define MOE_FFN_SKINNY 2      /* weight-streaming path for at most 16 rows per expert (decode); needs T <= 16, d <= 4096 */
 
+/* layout of the expert weight arrays w1, w3, w2 that the caller passes to the expert-FFN entry points */
+#define MOE_WEIGHTS_ROWMAJOR 0  /* [N,I,d] / [N,d,I] row-major: not consumed by any kernel of this build (pack them first) */
+#define MOE_WEIGHTS_PACKED   1  /* the MFMA-fragment order written by moe_pack_weights */
+
 typedef struct moe_shape {
-    int32_t T;         /* tokens in the batch */
-    int32_t d;         /* hidden size */
-    int32_t N;         /* routed experts in the layer */
-    int32_t k;         /* experts selected per token */
-    int32_t I;         /* expert FFN inner size */
-    int32_t ffn_path;  /* MOE_FFN_* */
+    int32_t T;              /* tokens in the batch */
+    int32_t d;              /* hidden size */
+    int32_t N;              /* routed experts in the layer */
+    int32_t k;              /* experts selected per token */
+    int32_t I;              /* expert FFN inner size */
+    int32_t ffn_path;       /* MOE_FFN_* */
+    int32_t weight_layout;  /* MOE_WEIGHTS_*: what the caller says w1, w3, w2 hold.  The library cannot tell the two
+                               layouts apart by looking, so the caller states it: a zero-initialised shape (row-major)
+                               makes moe_expert_ffn* return MOE_EUNSUPPORTED instead of multiplying garbage.  Read by
+                               the expert-FFN entry points only. */
 } moe_shape;
 
 const char *moe_strerror(int code);
@@ -145,7 +153,8 @@ int moe_pack_weights(int n_mats, int rows, int K, const void *src, void *dst, vo
  * bf16 inputs, fp32 accumulation; the inner activation is rounded to bf16 once before the second
  * product.  Rows of experts that are masked off are not written.
  * h [T,d] bf16; perm [T*k], offsets [N+1], counts [N] int32 as produced by moe_route (or
- * moe_dense_route); w1, w3: [N,I,d] bf16 and w2: [N,d,I] bf16, all three PACKED by moe_pack_weights;
+ * moe_dense_route); w1, w3: [N,I,d] bf16 and w2: [N,d,I] bf16, all three PACKED by moe_pack_weights, and
+ * s->weight_layout = MOE_WEIGHTS_PACKED says so (any other value: MOE_EUNSUPPORTED, nothing launched);
  * expert_mask [N] uint8 (NULL = all on);
  * y [T*k,d] bf16 out, in permuted row order: all [device].
  * The host cannot see the tables, so they are trusted: the kernels index h, y and the workspace with perm,

@@ -25,7 +25,7 @@ EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_work
 
 class MoeShape(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("N", C.c_int32), ("k", C.c_int32), ("I", C.c_int32),
-                ("ffn_path", C.c_int32)]
+                ("ffn_path", C.c_int32), ("weight_layout", C.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -70,8 +70,13 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def shape(T: int, d: int, N: int, k: int, I: int, ffn_path: int = FFN_AUTO) -> MoeShape:
-    return MoeShape(T, d, N, k, I, ffn_path)
+WEIGHTS_ROWMAJOR, WEIGHTS_PACKED = 0, 1      # MOE_WEIGHTS_* of include/moe_layer.h
+
+
+def shape(T: int, d: int, N: int, k: int, I: int, ffn_path: int = FFN_AUTO, weight_layout: int = WEIGHTS_PACKED) -> MoeShape:
+    """weight_layout states what the expert weight tensors passed with this shape hold; the default is what
+    moe_pack_weights (LayerWeights.upload) produces, the only layout the kernels read."""
+    return MoeShape(T, d, N, k, I, ffn_path, weight_layout)
 
 
 def workspace_bytes(s: MoeShape) -> int:

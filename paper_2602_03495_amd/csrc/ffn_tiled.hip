@@ -36,6 +36,8 @@
 // and of the number of K splits only, so results are reproducible for given inputs.
 #include "moe_common.h"
 
+#include <cstdlib>
+
 #define TM MOE_TILE_M     // token rows per tile
 #define NUM_XCD MOE_NUM_XCD
 #define TILED_THREADS 512
@@ -119,11 +121,36 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
     for (int j = 0; j < n_dn; ++j) tab[first_dn + j] = make_int4(e, first_dn, n_dn, 0);
 }
 
+#ifdef MOE_TRACE
+// development builds only: per-block begin / end times and placement, for a timeline of a launch
+__device__ unsigned long long *g_moe_trace = nullptr;
+extern "C" int moe_debug_set_trace(unsigned long long *p)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_moe_trace), &p, sizeof(p)) == hipSuccess ? 0 : -1;
+}
+#define MOE_TRACE_BEGIN() const unsigned long long trace_t0_ = wall_clock64()
+#define MOE_TRACE_END(mode_, e_, nrows_, nt_)                                                                   \
+    do {                                                                                                        \
+        if (g_moe_trace != nullptr && threadIdx.x == 0) {                                                       \
+            unsigned hw_;                                                                                       \
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_));                                   \
+            unsigned xcc_;                                                                                      \
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_));                                 \
+            unsigned long long *r_ = g_moe_trace + 8ull * (blockIdx.x + (mode_) * 65536ull);                    \
+            r_[0] = trace_t0_; r_[1] = wall_clock64(); r_[2] = hw_; r_[3] = xcc_;                               \
+            r_[4] = (e_); r_[5] = (nrows_); r_[6] = (nt_); r_[7] = 1;                                           \
+        }                                                                                                       \
+    } while (0)
+#else
+#define MOE_TRACE_BEGIN()
+#define MOE_TRACE_END(mode_, e_, nrows_, nt_)
+#endif
+
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.
 // Weight tile of a block: 8 waves x NF fragments x 16 rows.  NTT = 16-row token subtiles computed (rows past
 // nrows are clamped copies whose results are dropped).
-template <int MODE, int NF, int NTT, int NSETS, bool FENCED>
+template <int MODE, int NF, int NTT, int NSETS, bool FENCED, int WAVES>
 __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int I, int k, const uint16_t *__restrict__ xsrc,
                                           const int32_t *__restrict__ perm, const uint16_t *__restrict__ wa,
                                           const uint16_t *__restrict__ wb, uint16_t *__restrict__ out, int e, int nt,
@@ -131,7 +158,8 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 {
     constexpr int HF = MODE == 0 ? NF / 2 : NF;           // fragments per matrix per wave
     constexpr int WAVE_COLS = HF * 16;                     // output columns a wave produces
-    constexpr int NT_COLS = 8 * WAVE_COLS;                 // output columns per block
+    constexpr int NT_COLS = WAVES * WAVE_COLS;             // output columns per block
+    constexpr int RPP = WAVES * 8;                         // token rows one pass of the loader covers (8 threads per row)
     const int K = MODE == 0 ? d : I;
     const int NOUT = MODE == 0 ? I : d;
     const int n0 = nt * NT_COLS;
@@ -154,13 +182,13 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
         wp0 = reinterpret_cast<const char *>(wa + mat);
         wp1 = MODE == 0 ? reinterpret_cast<const char *>(wb + mat) : wp0;
     }
-    // ---- token tile loader: thread -> rows tid/8 + 64 j (j < 2), 16-byte chunk tid%8 of the 128-byte k64 segment
+    // ---- token tile loader: thread -> rows tid/8 + RPP j (j < XJ), 16-byte chunk tid%8 of the 128-byte k64 segment
     const int xc = tid & 7;
-    constexpr int XJ = NTT > 4 ? 2 : 1;                    // 64-row halves of the token tile that are in use
+    constexpr int XJ = (NTT * 16 + RPP - 1) / RPP;         // loader passes over the token rows that are in use
     uint32_t xo[XJ];
 #pragma unroll
     for (int j = 0; j < XJ; ++j) {
-        int r = (tid >> 3) + 64 * j;
+        int r = (tid >> 3) + RPP * j;
         if (r >= nrows) r = nrows - 1;
         if (MODE == 0)                                      // byte offsets: T*d < 2^31 elements keeps them in 32 bits
             xo[j] = ((uint32_t)(perm[row0 + r] / k) * (uint32_t)d + xc * 8) * 2u;
@@ -174,7 +202,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     // must hit 16 different 16-byte bank groups: i ^ g keeps that (4 clocks per read instead of 8 for plain rows), while
     // the 8 chunks of one row, which one store instruction of the loader carries in 8 adjacent lanes, land in 8
     // different bank groups (16 clocks per store instead of 64 for the unswizzled fragment order).
-    uint16_t *xw = &Xs[0][xc >> 2][(tid >> 7) * 512 + ((xc & 3) * 16 + (((tid >> 3) & 15) ^ (xc & 3) ^ (xc >> 2) * 8)) * 8];   // + buffer * 2*TM*32 + j * 64 rows
+    uint16_t *xw = &Xs[0][xc >> 2][(tid >> 7) * 512 + ((xc & 3) * 16 + (((tid >> 3) & 15) ^ (xc & 3) ^ (xc >> 2) * 8)) * 8];   // + buffer * 2*TM*32 + j * RPP rows
     const uint16_t *xrd0 = &Xs[0][0][(lg * 16 + (li ^ lg)) * 8];       // + buffer * 2*TM*32 + t * 16 rows
     const uint16_t *xrd1 = &Xs[0][1][(lg * 16 + (li ^ lg ^ 8)) * 8];
 
@@ -214,7 +242,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #define XSTORE(buf)                                                                              \
     do {                                                                                         \
         _Pragma("unroll") for (int j = 0; j < XJ; ++j)                                           \
-            *reinterpret_cast<u32x4 *>(xw + (buf) * (2 * TM * 32) + j * (64 * 32)) = xg[buf][j]; \
+            *reinterpret_cast<u32x4 *>(xw + (buf) * (2 * TM * 32) + j * (RPP * 32)) = xg[buf][j]; \
     } while (0)
 #define XREAD(buf, half)                                                                         \
     do {                                                                                         \
@@ -350,8 +378,8 @@ __device__ __forceinline__ bool up_items_narrow(int items)
 
 // NTT_MAX bounds the token subtiles a tile of this launch can need (from T); the block then runs the smallest
 // body that covers its own rows, so a sparsely filled tile costs MFMA work for the rows it has.
-template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS, bool FENCED>
-__global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
+template <int MODE, int NF, int NTT_MAX, bool DIRECT, int NSETS, bool FENCED, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void ffn_tiled_kernel(
     int d, int I, int k, int N, const uint16_t *__restrict__ xsrc,   // MODE 0: h [T,d]; MODE 1: act [R,I]
     const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, const int32_t *__restrict__ counts,
     const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
@@ -362,13 +390,14 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
     // The up projection with its widest tile (NF = 4: 256 inner columns) can run its items with half that width instead:
     // also decided on the device (up_items_narrow).
-    constexpr bool CAN_NARROW = MODE == 0 && NF == 4;
-    constexpr int NT_COLS = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
+    constexpr bool CAN_NARROW = MODE == 0 && NF == 4 && WAVES == 8;
+    constexpr int NT_COLS = WAVES * 16 * (MODE == 0 ? NF / 2 : NF);
     int n_ntc = ((MODE == 0 ? I : d) + NT_COLS - 1) / NT_COLS;   // column tiles
     bool narrow = false;
 
     // ---- which item: (expert, token tile, column tile, K split).  The number of K splits follows from the number of
     // tiles that have work, which only the device knows (counts and mask live there)
+    MOE_TRACE_BEGIN();
     int e, mt, nt, nsp = 1;
     if (DIRECT) {
         // at most one token tile per expert (T <= 128): no schedule has been built
@@ -406,12 +435,25 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
     const int row0 = offsets[e] + mt * tmk;
     int nrows = counts[e] - mt * tmk;
     nrows = nrows > tmk ? tmk : nrows;
-#define BODY_NF(nf_, n) tile_body<MODE, nf_, n, NSETS, FENCED>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
+#define BODY_NS(nf_, n, ns_) tile_body<MODE, nf_, n, ns_, FENCED, WAVES>(Xs, d, I, k, xsrc, perm, wa, wb, out, e, nt, row0, nrows, sp, nsp, part, R)
+#define BODY_NF(nf_, n) BODY_NS(nf_, n, NSETS)
+    // tiles with few token rows do little arithmetic per weight byte: their speed is the speed of the weight stream, so
+    // they prefetch further ahead (8 register sets instead of 4; the accumulators of a short tile leave the room)
+#ifdef MOE_DEEP_SMALL
+    const bool deep_ok = NSETS == 4 && WAVES == 8 && (((MODE == 0 ? d : I) / 32 / nsp) % 8) == 0;
+#else
+    const bool deep_ok = false;
+#endif
+#define BODY_SMALL(nf_, n)                                         \
+    do {                                                           \
+        if (deep_ok) BODY_NS(nf_, n, 8);                           \
+        else BODY_NF(nf_, n);                                      \
+    } while (0)
 #define BODIES(nf_)                                                \
     do {                                                           \
-        if (NTT_MAX == 1 || nrows <= 16) BODY_NF(nf_, 1);          \
-        else if (NTT_MAX == 2 || nrows <= 32) BODY_NF(nf_, 2);     \
-        else if (NTT_MAX == 4 || nrows <= 64) BODY_NF(nf_, 4);     \
+        if (NTT_MAX == 1 || nrows <= 16) BODY_SMALL(nf_, 1);       \
+        else if (NTT_MAX == 2 || nrows <= 32) BODY_SMALL(nf_, 2);  \
+        else if (NTT_MAX == 4 || nrows <= 64) BODY_SMALL(nf_, 4);  \
         else if (nrows <= 96) BODY_NF(nf_, 6);                     \
         else if (MODE == 1 && nrows <= 112) BODY_NF(nf_, 7);       \
         else BODY_NF(nf_, 8);                                      \
@@ -424,12 +466,16 @@ __global__ __launch_bounds__(TILED_THREADS, 2) void ffn_tiled_kernel(
         }
         if (narrow) {
             BODIES(2);
+            MOE_TRACE_END(MODE, e, nrows, nt);
             return;
         }
     }
     BODIES(NF);
+    MOE_TRACE_END(MODE, e, nrows, nt);
 #undef BODIES
+#undef BODY_SMALL
 #undef BODY_NF
+#undef BODY_NS
 }
 
 // y[p,:] = bf16( sum over the K splits, in split order ), when the down projection of this launch split K (the same
@@ -464,21 +510,21 @@ __global__ __launch_bounds__(256) void tiled_finish_kernel(int d, int R, int N, 
     }
 }
 
-template <int MODE, int NF, int NTT, bool DIRECT, int NSETS, bool FENCED>
+template <int MODE, int NF, int NTT, bool DIRECT, int NSETS, bool FENCED, int WAVES>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
                          const uint8_t *mask, uint16_t *out, int nsp_max, float *part, hipStream_t st)
 {
-    constexpr int cols = 8 * 16 * (MODE == 0 ? NF / 2 : NF);
+    constexpr int cols = WAVES * 16 * (MODE == 0 ? NF / 2 : NF);
     const long n_ntc = ((MODE == 0 ? s->I : s->d) + cols - 1) / cols;
     const int R = s->T * s->k;
     // blocks for the most items the device-side choice of K splits can produce: with every tile at work it takes the
     // fewest splits that reach 256 items, with fewer tiles at work there are fewer items, so this bound covers both
     long n_nt = n_ntc * nsp_max;
-    if (MODE == 0 && NF == 4) n_nt = (s->I + cols / 2 - 1) / (cols / 2);   // ... or the half-width items of the up projection
+    if (MODE == 0 && NF == 4 && WAVES == 8) n_nt = (s->I + cols / 2 - 1) / (cols / 2);   // ... or the half-width items of the up projection
     const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
-    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS, FENCED>), grid, dim3(TILED_THREADS), 0, st, s->d, s->I, s->k,
+    hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS, FENCED, WAVES>), grid, dim3(WAVES * 64), 0, st, s->d, s->I, s->k,
                        s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
 }
 
@@ -489,13 +535,18 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
 // ahead (8 register sets, K permitting; 16 measured no better: the token loads, two stages ahead, sit between the
 // weight loads in the in-order vmcnt queue and bound the useful depth).
 template <int MODE>
-static void dispatch_tiled(const moe_shape *s, int nf, long max_mt, const uint16_t *x, const int32_t *perm,
+static void dispatch_tiled(const moe_shape *s, int nf, int waves, long max_mt, const uint16_t *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *counts, const uint16_t *wa, const uint16_t *wb,
                            const int32_t *sched, const uint8_t *mask, uint16_t *out, int nsp_max, float *part, hipStream_t st)
 {
     const int K = MODE == 0 ? s->d : s->I;
     const bool deep = K % (256 * nsp_max) == 0 && K >= 2048;   // a short K does not pay for the longer prologue
-#define GO(NF_, NTT_, D_, NS_, F_) launch_tiled<MODE, NF_, NTT_, D_, NS_, F_>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st)
+#define GO(NF_, NTT_, D_, NS_, F_) launch_tiled<MODE, NF_, NTT_, D_, NS_, F_, 8>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st)
+    if (waves == 4) {
+        // two independent 4-wave blocks per compute unit (scheduled launches with full-height tiles only)
+        launch_tiled<MODE, 4, 8, false, 4, false, 4>(s, max_mt, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, st);
+        return;
+    }
 #define GO3(NTT_, D_)                                                          \
     do {                                                                       \
         if constexpr (MODE == 1) {                                             \
@@ -542,9 +593,14 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
     const long est_mt = (R + TM - 1) / TM > (N < R ? N : R) ? (R + TM - 1) / TM : (N < R ? N : R);
 
     // the down projection's tile shape (needed by the schedule, which the up stage builds for both)
-    const int nf = s->T <= MOE_SKINNY_MAX_T ? 1
-                   : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
-    const int n_ntc = (d + 128 * nf - 1) / (128 * nf);
+    int nf = s->T <= MOE_SKINNY_MAX_T ? 1
+             : est_mt * ((d + 511) / 512) >= 256 ? 4 : est_mt * ((d + 255) / 256) >= 256 ? 2 : 1;
+    // blocks of 4 waves, two of them per compute unit, for scheduled launches (experiment switch)
+    static const int env_up = getenv("MOE_TILED_WAVES_UP") ? atoi(getenv("MOE_TILED_WAVES_UP")) : 0;
+    static const int env_dn = getenv("MOE_TILED_WAVES_DOWN") ? atoi(getenv("MOE_TILED_WAVES_DOWN")) : 0;
+    const int waves_up = s->T > TM && env_up == 4 ? 4 : 8;
+    const int waves_down = s->T > TM && env_dn == 4 && nf == 4 ? 4 : 8;
+    const int n_ntc = (d + 16 * waves_down * nf - 1) / (16 * waves_down * nf);
     // The tile tables are built at the start of every call, also of one that runs the down stage alone: that call then
     // never reads a table that an earlier call did not build or built from other counts or another mask.
     if (s->T > TM) {
@@ -553,7 +609,7 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
         MOE_CHECK_LAUNCH();
     }
     if (stages & MOE_FFN_STAGE_UP) {
-        dispatch_tiled<0>(s, 4, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
+        dispatch_tiled<0>(s, 4, waves_up, max_mt, (const uint16_t *)h, perm, offsets, counts, (const uint16_t *)w1,
                           (const uint16_t *)w3, sched, expert_mask, act, 1, nullptr, st);
         MOE_CHECK_LAUNCH();
     }
@@ -564,7 +620,7 @@ int moe_ffn_tiled_impl(const moe_shape *s, const void *h, const int32_t *perm, c
         // knows counts and mask)
         const int nsp_max = moe_tiled_down_max_splits(s);
         float *part = (float *)((char *)workspace + L.partial);
-        dispatch_tiled<1>(s, nf, max_mt_down, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
+        dispatch_tiled<1>(s, nf, waves_down, max_mt_down, (const uint16_t *)act, perm, offsets, counts, (const uint16_t *)w2,
                           (const uint16_t *)nullptr, sched_down, expert_mask, (uint16_t *)y, nsp_max, part, st);
         MOE_CHECK_LAUNCH();
         if (nsp_max > 1) {

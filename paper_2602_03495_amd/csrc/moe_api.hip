@@ -72,7 +72,7 @@ const char *moe_strerror(int code)
     switch (code) {
     case MOE_OK: return "ok";
     case MOE_EINVAL: return "invalid argument (null or misaligned pointer, or a size out of range)";
-    case MOE_EUNSUPPORTED: return "request not supported by this build (shape outside the chosen FFN path)";
+    case MOE_EUNSUPPORTED: return "request not supported by this build (shape outside the chosen FFN path, or expert weights not declared as packed by moe_pack_weights: set moe_shape.weight_layout = MOE_WEIGHTS_PACKED)";
     case MOE_ELAUNCH: return "HIP kernel launch failed";
     case MOE_EWORKSPACE: return "workspace pointer must be 256-byte aligned";
     case MOE_ETOOLARGE: return "shape needs more scratch than the library's static scratch array holds (see moe_static_scratch_bytes)";
@@ -129,6 +129,8 @@ int moe_expert_ffn_stage(const moe_shape *s, const void *h, const int32_t *perm,
     if (!h || !perm || !offsets || !counts || !w1 || !w3 || !w2 || !y || !workspace) return MOE_EINVAL;
     if (!aligned16(h) || !aligned16(w1) || !aligned16(w3) || !aligned16(w2) || !aligned16(y)) return MOE_EINVAL;
     if (((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    // every kernel reads the weights in the packed fragment order; row-major arrays would be multiplied as garbage
+    if (s->weight_layout != MOE_WEIGHTS_PACKED) return MOE_EUNSUPPORTED;
     int path = s->ffn_path;
     // the decode path keeps a wave's share of the hidden dimension in registers: at most 4096 wide
     if (path == MOE_FFN_AUTO)
@@ -154,6 +156,7 @@ int moe_expert_ffn_static(const moe_shape *s, const void *h, const int32_t *perm
 {
     int rc = check_shape(s, true);
     if (rc != MOE_OK) return rc;
+    if (s->weight_layout != MOE_WEIGHTS_PACKED) return MOE_EUNSUPPORTED;
     if (moe_ws(s).total > MOE_STATIC_SCRATCH_BYTES) return MOE_ETOOLARGE;
     void *scratch = nullptr;
     rc = static_scratch(&scratch);

@@ -14,7 +14,7 @@ MOE_OK, MOE_EINVAL, MOE_EUNSUPPORTED, MOE_ELAUNCH, MOE_EWORKSPACE = 0, -1, -2, -
 
 
 class Shape(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("T", "d", "N", "k", "I", "ffn_path")]
+    _fields_ = [(n, C.c_int32) for n in ("T", "d", "N", "k", "I", "ffn_path", "weight_layout")]
 
 
 def declared_functions():
@@ -46,7 +46,7 @@ def test_library_exports_every_declared_symbol(lib):
 def test_binding_lists_the_same_symbols():
     from paper_2602_03495_amd import binding
     assert sorted(binding.EXPORTS) == declared_functions()
-    assert C.sizeof(binding.MoeShape) == 24
+    assert C.sizeof(binding.MoeShape) == 28 == C.sizeof(Shape)
 
 
 def test_strerror(lib):
@@ -89,9 +89,9 @@ def test_entry_points_reject_null_and_misaligned_pointers_before_launching(lib):
     assert lib.moe_predict_workload(C.byref(s), p, p, p, z, 2, p, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
     assert lib.moe_expert_ffn(C.byref(s), p, p, p, p, p, p, z, z, p, p, z) == MOE_EINVAL          # no w2
     assert lib.moe_expert_ffn(C.byref(s), p, p, p, p, p, p, p, z, p, C.c_void_p(0x1010), z) == MOE_EWORKSPACE
-    bad_path = Shape(16, 256, 8, 2, 512, 5)
+    bad_path = Shape(16, 256, 8, 2, 512, 5, 1)
     assert lib.moe_expert_ffn(C.byref(bad_path), p, p, p, p, p, p, p, z, p, p, z) == MOE_EINVAL
-    skinny_big = Shape(64, 256, 8, 2, 512, 2)     # the skinny path takes at most 16 tokens
+    skinny_big = Shape(64, 256, 8, 2, 512, 2, 1)  # the skinny path takes at most 16 tokens
     assert lib.moe_expert_ffn(C.byref(skinny_big), p, p, p, p, p, p, p, z, p, p, z) == MOE_EUNSUPPORTED
     assert lib.moe_combine(C.byref(s), p, p, p, p, z, z, 0, z, z, z) == MOE_EINVAL                # no out
     assert lib.moe_combine(C.byref(s), p, p, p, p, z, p, 0, z, p, z) == MOE_EINVAL                # shared_y without count
@@ -141,3 +141,20 @@ def test_append_shared_rejects_bad_arguments_before_launching(lib):
         assert ap(2, z, z, *(ok[:i] + (z,) + ok[i + 1:])) == MOE_EINVAL
     wide = Shape(16, 256, 127, 2, 512, 0)
     assert lib.moe_append_shared(C.byref(wide), 2, z, z, *ok, z) == MOE_EINVAL     # N + n_shared > 128 experts
+
+
+def test_expert_ffn_refuses_weights_not_declared_as_packed(lib):
+    # the kernels read the weights in the fragment order of moe_pack_weights only; the library cannot see which layout
+    # an array has, so the shape carries the caller's statement and anything but "packed" is refused before any launch
+    # (a zero-initialised shape says row-major).  All other arguments of these calls are valid-looking.
+    p, z = C.c_void_p(0x1000), C.c_void_p(0)
+    for layout in (0, 2, -1):
+        s = Shape(16, 256, 8, 2, 512, 0, layout)
+        assert lib.moe_expert_ffn(C.byref(s), p, p, p, p, p, p, p, z, p, p, z) == MOE_EUNSUPPORTED
+        assert lib.moe_expert_ffn_stage(C.byref(s), p, p, p, p, p, p, p, z, p, p, 1, z) == MOE_EUNSUPPORTED
+        assert lib.moe_expert_ffn_static(C.byref(s), p, p, p, p, p, p, p, z, p, z) == MOE_EUNSUPPORTED
+    lib.moe_strerror.restype = C.c_char_p
+    assert b"moe_pack_weights" in lib.moe_strerror(MOE_EUNSUPPORTED)
+    # the tag is read by the expert-FFN calls only
+    n = C.c_size_t(0)
+    assert lib.moe_workspace_bytes(C.byref(Shape(16, 256, 8, 2, 512, 0, 0)), C.byref(n)) == MOE_OK
