@@ -222,7 +222,7 @@ def time_graph_replays(torch, L, hd, dw, mask_d, steps, warmup):
     return time.perf_counter() - t0
 
 
-def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
+def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20, merged=True):
     """One JSON-able record per batch size: the whole step (route, masked routed FFN, shared experts, combine) with HIP
     events between the calls, and the FFN's share of the bf16 MFMA / HBM peaks."""
     cfg = wl.CONFIGS[name]
@@ -280,7 +280,7 @@ def survey_config(torch, B, Lm, wl, name, Ts, mask_kind, steps=20):
                "active_experts": active, "rows_on": rows_on}
         rec["bound"] = "mfma" if rec["experts_mfma_frac"] >= rec["experts_hbm_frac"] else "hbm"
         rec["bound_frac"] = max(rec["experts_mfma_frac"], rec["experts_hbm_frac"])     # max(F / (t P_mfma), B / (t BW))
-        if L.n_merged:
+        if L.n_merged and merged:
             # the same layer with its shared experts inside the grouped launches (moe_append_shared)
             xm = L.merged_mask(md)
             mstep = lambda: L.forward_merged(hd, dw, xm)
@@ -401,6 +401,74 @@ def survey_rows_per_expert(torch, B, Lm, wl, steps=20):
     return out
 
 
+def timeline(torch, B, Lm, wl, spec):
+    """Per-block timeline of the two tiled expert-FFN launches of one shape (moe_debug_set_trace): how long blocks of
+    each tile height take, how evenly the compute units and the XCDs finish.  spec: SHAPE:TOKENS:MASK with MASK = all,
+    half (top half by this batch's workloads), rand6, or onlyE[,E...] (just those experts on)."""
+    name, T, mk = spec.split(":")
+    T = int(T)
+    cfg = wl.CONFIGS[name]
+    w1, w3, w2 = wl.expert_weights(cfg)
+    dw = Lm.LayerWeights.upload(wl.gate_weights(cfg), wl.gate_bias(cfg), w1, w3, w2)
+    L = Lm.MoeLayer(cfg, T, B.FFN_TILED)
+    hd = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=T))
+    L.route(hd, dw)
+    torch.cuda.synchronize()
+    counts = L.routing.counts.cpu().numpy()
+    if mk.startswith("only"):
+        mask = np.zeros(cfg.N, np.uint8)
+        mask[[int(e) for e in mk[4:].split(",")]] = 1
+    else:
+        mask = {"all": np.ones(cfg.N, np.uint8), "half": wl.mask_top_by_counts(counts, cfg.N // 2), "rand6": wl.mask_random(cfg, 6)}[mk]
+    md = torch.from_numpy(mask).cuda()
+    records = torch.zeros(2 * B.TRACE_MAX_BLOCKS * 8, dtype=torch.int64, device="cuda")
+    for _ in range(3):
+        L.expert_ffn(hd, dw, md)
+    torch.cuda.synchronize()
+    B.moe_debug_set_trace(records)
+    L.expert_ffn(hd, dw, md)
+    torch.cuda.synchronize()
+    B.moe_debug_set_trace(None)
+    tr = records.cpu().numpy().reshape(2, B.TRACE_MAX_BLOCKS, 8)
+    out = {"metric": "block timeline of the tiled expert FFN", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{name}-shaped layer, {T} tokens, mask {mk}"}, "counts_on": counts[mask.astype(bool)].tolist()}
+    for mode, nm in ((0, "up"), (1, "down")):
+        t = tr[mode]
+        t = t[t[:, 7] == 1]
+        if len(t) == 0:
+            continue
+        t0 = t[:, 0].min()
+        b, e = (t[:, 0] - t0) / 100.0, (t[:, 1] - t0) / 100.0
+        dur, rows, xcd = e - b, t[:, 5], t[:, 3] & 0xF
+        cu = xcd * 4096 + ((t[:, 2] >> 8) & 0xFFF)          # XCD, then shader engine / array / compute unit bits of HW_ID
+        span = float(e.max())
+        last = {}
+        for c, ee in zip(cu.tolist(), e.tolist()):
+            last[c] = max(last.get(c, 0.0), ee)
+        rec = {"blocks": int(len(t)), "compute_units_used": len(last), "span_us": span, "sum_of_block_us": float(dur.sum()),
+               "mean_busy_units": float(dur.sum() / span), "last_end_per_unit_us": {"mean": float(np.mean(list(last.values()))),
+                                                                                   "min": float(min(last.values())), "max": float(max(last.values()))},
+               "by_rows": [], "by_xcd": []}
+        for lo, hi in ((1, 16), (17, 32), (33, 64), (65, 96), (97, 128)):
+            m = (rows >= lo) & (rows <= hi)
+            if m.any():
+                rec["by_rows"].append({"rows": f"{lo}-{hi}", "blocks": int(m.sum()), "mean_us": float(dur[m].mean()),
+                                       "min_us": float(dur[m].min()), "max_us": float(dur[m].max())})
+        for x in range(8):
+            m = xcd == x
+            if m.any():
+                rec["by_xcd"].append({"xcd": x, "blocks": int(m.sum()), "last_end_us": float(e[m].max()), "sum_of_block_us": float(dur[m].sum()),
+                                      "mean_rows": float(rows[m].mean())})
+        out[nm] = rec
+        log(f"[bench] timeline {name} T={T} {nm}: {rec['blocks']} blocks on {rec['compute_units_used']} units, span {span:.1f} us, "
+            f"{rec['mean_busy_units']:.1f} units busy on average; units finish at {rec['last_end_per_unit_us']['mean']:.1f} us on average "
+            f"({rec['last_end_per_unit_us']['min']:.1f} .. {rec['last_end_per_unit_us']['max']:.1f})")
+        for r in rec["by_rows"]:
+            log(f"[bench]    tiles of {r['rows']:>7s} rows: {r['blocks']:5d} blocks, {r['mean_us']:6.1f} us each ({r['min_us']:.1f} .. {r['max_us']:.1f})")
+        log("[bench]    XCD finish times: " + " ".join(f"{r['last_end_us']:.0f}" for r in rec["by_xcd"]))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -420,6 +488,10 @@ def main():
                     help="time one layer shape at one batch size instead, e.g. deepseek:2048:half, qwen15:1:all, mixtral:2048:rand6 "
                          "(mask: all | half = top half by this batch's workloads | rand6); prints one JSON record; the run to "
                          "profile when per-shape kernel statistics or counters are wanted")
+    ap.add_argument("--timeline", default=None, metavar="SHAPE:TOKENS:MASK",
+                    help="per-block timeline of the tiled expert-FFN launches of one shape (block durations by tile height, "
+                         "finish times per compute unit and per XCD); MASK as for --one, or onlyE[,E...] for just those experts")
+    ap.add_argument("--one-merged", action="store_true", help="--one: also time the variant with the shared experts inside the grouped launches")
     ap.add_argument("--stack-layers", type=int, default=48)
     ap.add_argument("--stack-steps", type=int, default=256)
     ap.add_argument("--assign", action="store_true",
@@ -461,9 +533,13 @@ def main():
         log("[bench] calibration copy done: 5 x (1 GiB read + 1 GiB written)")
         return
 
+    if args.timeline:
+        print(json.dumps(timeline(torch, B, Lm, wl, args.timeline)), flush=True)
+        return
+
     if args.one:
         name, T1, mk = args.one.split(":")
-        rec = survey_config(torch, B, Lm, wl, name, [int(T1)], mk, steps=args.steps)[0]
+        rec = survey_config(torch, B, Lm, wl, name, [int(T1)], mk, steps=args.steps, merged=args.one_merged)[0]
         print(json.dumps({"metric": "MoE-layer step time, one shape", "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": f"{name}-shaped layer, {T1} tokens, mask {mk}"}, **rec}), flush=True)
         return

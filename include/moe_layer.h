@@ -278,6 +278,16 @@ int moe_res_vec_accumulate(int n, int d, const void *h_cur, const void *h_next, 
                            void *stream);
 int moe_res_vec_finish(int d, const double *acc_sum, int64_t n_total, float *res_vec, void *stream);
 
+/*
+ * Diagnostics (not a step of the method): timeline of the tiled expert-FFN launches.  With records != NULL, every
+ * block of the tiled up / down projection kernels launched afterwards on the current device writes one record of
+ * 8 uint64: {begin, end (100 MHz constant clock), HW_ID register, XCC_ID register, expert, token rows of the tile,
+ * column tile, 1} at records[8 * (block index + 65536 * projection)], projection 0 = up, 1 = down; blocks with an
+ * index of 65536 or more write nothing.  records [device]: 2 * 65536 * 8 uint64 (8 MiB), zeroed by the caller, who
+ * keeps it alive until moe_debug_set_trace(NULL).  One setting per device; launches on other streams see it too.
+ */
+int moe_debug_set_trace(unsigned long long *records);
+
 /* ------------------------------------------------------------------------------------------------------------
  * Host-side scheduling policies fed by the workload histograms (all pointers [host]; nothing touches the GPU).
  * ------------------------------------------------------------------------------------------------------------ */

@@ -20,7 +20,7 @@ EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_work
            "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
            "moe_expert_times", "moe_greedy_assign", "moe_cache_step", "moe_res_vec_workspace_bytes",
            "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict", "moe_append_shared",
-           "moe_expert_ffn_static", "moe_static_scratch_bytes"]
+           "moe_expert_ffn_static", "moe_static_scratch_bytes", "moe_debug_set_trace"]
 
 
 class MoeShape(C.Structure):
@@ -189,6 +189,16 @@ def moe_expert_ffn_static(s: MoeShape, h, perm, offsets, counts, w1, w3, w2, exp
                                               _ptr(y, torch.bfloat16), _stream())
     _check(rc, "moe_expert_ffn_static")
     return y
+
+
+TRACE_MAX_BLOCKS = 65536
+
+
+def moe_debug_set_trace(records: Optional[torch.Tensor]):
+    """records: zeroed int64 device tensor of 2 * TRACE_MAX_BLOCKS * 8 elements, or None to switch the timeline off."""
+    if records is not None and (records.dtype != torch.int64 or records.numel() < 2 * TRACE_MAX_BLOCKS * 8):
+        raise MoeError("timeline buffer: int64, 2 * 65536 * 8 elements")
+    _check(load_library().moe_debug_set_trace(_ptr(records)), "moe_debug_set_trace")
 
 
 def static_scratch_bytes() -> int:

@@ -121,30 +121,28 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
     for (int j = 0; j < n_dn; ++j) tab[first_dn + j] = make_int4(e, first_dn, n_dn, 0);
 }
 
-#ifdef MOE_TRACE
-// development builds only: per-block begin / end times and placement, for a timeline of a launch
+// Diagnostics: when a record buffer has been set (moe_debug_set_trace), thread 0 of every block of a tiled launch
+// writes its begin / end time (constant 100 MHz clock), where it ran and what it worked on: the timeline of a launch.
+// Costs one clock read per block and one scalar load of the pointer when unset.
+#define MOE_TRACE_MAX_BLOCKS 65536
 __device__ unsigned long long *g_moe_trace = nullptr;
-extern "C" int moe_debug_set_trace(unsigned long long *p)
+extern "C" int moe_debug_set_trace(unsigned long long *records)
 {
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_moe_trace), &p, sizeof(p)) == hipSuccess ? 0 : -1;
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_moe_trace), &records, sizeof(records)) == hipSuccess ? MOE_OK : MOE_ELAUNCH;
 }
 #define MOE_TRACE_BEGIN() const unsigned long long trace_t0_ = wall_clock64()
 #define MOE_TRACE_END(mode_, e_, nrows_, nt_)                                                                   \
     do {                                                                                                        \
-        if (g_moe_trace != nullptr && threadIdx.x == 0) {                                                       \
-            unsigned hw_;                                                                                       \
+        unsigned long long *tr_ = g_moe_trace;                                                                  \
+        if (tr_ != nullptr && threadIdx.x == 0 && blockIdx.x < MOE_TRACE_MAX_BLOCKS) {                          \
+            unsigned hw_, xcc_;                                                                                 \
             asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_));                                   \
-            unsigned xcc_;                                                                                      \
             asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_));                                 \
-            unsigned long long *r_ = g_moe_trace + 8ull * (blockIdx.x + (mode_) * 65536ull);                    \
+            unsigned long long *r_ = tr_ + 8ull * (blockIdx.x + (mode_) * (unsigned long long)MOE_TRACE_MAX_BLOCKS); \
             r_[0] = trace_t0_; r_[1] = wall_clock64(); r_[2] = hw_; r_[3] = xcc_;                               \
             r_[4] = (e_); r_[5] = (nrows_); r_[6] = (nt_); r_[7] = 1;                                           \
         }                                                                                                       \
     } while (0)
-#else
-#define MOE_TRACE_BEGIN()
-#define MOE_TRACE_END(mode_, e_, nrows_, nt_)
-#endif
 
 // MODE 0: up (W1|W3 + SwiGLU -> act); a wave owns NF/2 fragments of W1 and the same NF/2 of W3.
 // MODE 1: down (W2 -> y); a wave owns NF consecutive fragments of W2.

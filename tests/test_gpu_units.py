@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import OUT_TOL, rel_err
+from helpers import OUT_TOL, make_host_layer, rel_err
 from paper_2602_03495_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -114,3 +114,41 @@ def test_combine_alone_matches_the_weighted_sum(gpu):
     # without shared rows and with everything masked off the output is exactly zero
     B.moe_combine(s, Lm.to_device_bf16(y), dev(idx), dev(w), dev(inv), dev(np.zeros(N, np.uint8)), None, 0, None, out)
     assert float(out.float().abs().max()) == 0.0
+
+
+def test_block_timeline_records_every_block_of_both_tiled_launches(gpu):
+    # diagnostics: with a record buffer set, each block of the tiled up / down launches that had a tile to work on
+    # writes one record; the results of the layer are the same with and without it
+    B, Lm = gpu
+    cfg = wl.scaled(wl.CONFIGS["mixtral"], d=512, I=1792)
+    T = 300
+    hl = make_host_layer(cfg)
+    dw = Lm.LayerWeights.upload(hl.gate_w, hl.bias, hl.w1, hl.w3, hl.w2)
+    L = Lm.MoeLayer(cfg, T, B.FFN_TILED)
+    hd = Lm.to_device_bf16(wl.hidden_states(cfg, T))
+    L.route(hd, dw)
+    L.expert_ffn(hd, dw, None)
+    want = L.y.clone()
+    records = torch.zeros(2 * B.TRACE_MAX_BLOCKS * 8, dtype=torch.int64, device="cuda")
+    B.moe_debug_set_trace(records)
+    L.expert_ffn(hd, dw, None)
+    torch.cuda.synchronize()
+    B.moe_debug_set_trace(None)
+    assert torch.equal(L.y.view(torch.int16), want.view(torch.int16))
+    tr = records.cpu().numpy().reshape(2, B.TRACE_MAX_BLOCKS, 8)
+    counts = L.routing.counts.cpu().numpy()
+    for mode in (0, 1):
+        t = tr[mode][tr[mode][:, 7] == 1]
+        assert len(t) > 0
+        assert np.all(t[:, 1] >= t[:, 0]) and np.all((t[:, 5] >= 1) & (t[:, 5] <= 128))
+        assert set(t[:, 4].tolist()) == set(np.nonzero(counts)[0].tolist())
+        # per column tile, the token tiles of an expert cover its rows exactly once (the tile height is the kernel's choice)
+        for col_tile in set(t[:, 6].tolist()):
+            part = t[t[:, 6] == col_tile]
+            for e in np.nonzero(counts)[0]:
+                assert int(part[part[:, 4] == e][:, 5].sum()) == int(counts[e]), (mode, col_tile, e)
+    # switched off: nothing is written any more
+    records.zero_()
+    L.expert_ffn(hd, dw, None)
+    torch.cuda.synchronize()
+    assert not bool(records.any())
