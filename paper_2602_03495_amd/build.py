@@ -7,7 +7,8 @@ import subprocess
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-LIB = os.path.join(PKG, "libmoe_mi355x.so")
+# the in-tree library; MOE_LIB names another build of the same sources (e.g. one made with other MOE_EXTRA_HIPCC_FLAGS)
+LIB = os.environ.get("MOE_LIB") or os.path.join(PKG, "libmoe_mi355x.so")
 
 
 def sources():

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
                                                                         int32_t *__restrict__ sched_up,
                                                                         int32_t *__restrict__ sched_down)
 {
-    __shared__ int wsum[3][2], wtot[2][2];
+    __shared__ int wsum[3][2], wtot[4][2];
     const int e = threadIdx.x, w = e >> 6;
     const int c = (e < N && counts[e] > 0 && (mask == nullptr || mask[e] != 0)) ? counts[e] : 0;
     const int n128 = (c + 127) / 128, n112 = (c + 111) / 112, n96 = (c + 95) / 96;
@@ -116,7 +116,19 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void tile_schedule_kernel(int N, c
         sched_down[2] = sched_down[3] = 0;
     }
     int4 *tab = reinterpret_cast<int4 *>(sched_up + 4);
+#ifdef MOE_RAGGED_LAST
+    {
+        // full tiles of all experts first, then the ragged last tiles: a group is {expert, first list entry, tiles, first tile of the expert}
+        const int nfull = c / TM, rag = (c % TM) != 0 ? 1 : 0;
+        int tot_full, tot_rag;
+        const int first_full = block_exclusive_scan(nfull, wtot[2], &tot_full);
+        const int first_rag = tot_full + block_exclusive_scan(rag, wtot[3], &tot_rag);
+        for (int j = 0; j < nfull; ++j) tab[first_full + j] = make_int4(e, first_full, nfull, 0);
+        if (rag) tab[first_rag] = make_int4(e, first_rag, 1, nfull);
+    }
+#else
     for (int j = 0; j < n128; ++j) tab[first_up + j] = make_int4(e, first_up, n128, 0);
+#endif
     tab = reinterpret_cast<int4 *>(sched_down + 4);
     for (int j = 0; j < n_dn; ++j) tab[first_dn + j] = make_int4(e, first_dn, n_dn, 0);
 }
@@ -221,13 +233,18 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
     // Weight steps and token stages are loaded strictly in ring order, so one running position each replaces a
     // modulo per load: kw = k32 step of the next weight load, kx = k64 stage of the next token load.
     int kw = 2 * st0, kx = st0;
+#ifdef MOE_NT_WEIGHTS
+#define MOE_WLD(p) __builtin_nontemporal_load(p)
+#else
+#define MOE_WLD(p) (*(p))
+#endif
 #define WLOAD(set, s)                                                                            \
     do {                                                                                         \
         const size_t ko_ = (size_t)kw * 1024;                                                    \
         kw = kw + 1 == nk ? 0 : kw + 1;                                                          \
         _Pragma("unroll") for (int f = 0; f < HF; ++f) {                                         \
-            wr[set][f] = *reinterpret_cast<const u32x4 *>(wp0 + (f * rb_stride * 2 + ko_) + wlane); \
-            if (MODE == 0) wr[set][f + HF] = *reinterpret_cast<const u32x4 *>(wp1 + (f * rb_stride * 2 + ko_) + wlane); \
+            wr[set][f] = MOE_WLD(reinterpret_cast<const u32x4 *>(wp0 + (f * rb_stride * 2 + ko_) + wlane)); \
+            if (MODE == 0) wr[set][f + HF] = MOE_WLD(reinterpret_cast<const u32x4 *>(wp1 + (f * rb_stride * 2 + ko_) + wlane)); \
         }                                                                                        \
     } while (0)
 #define XLOAD(set, st)                                                                           \
@@ -327,6 +344,7 @@ __device__ __forceinline__ void tile_body(uint16_t (*Xs)[2][TM * 32], int d, int
 #undef XSTORE
 #undef XLOAD
 #undef WLOAD
+#undef MOE_WLD
 
     // ---- epilogue: in every 16x16 tile a lane holds weight rows 4*lg + 0..3 (= output columns) of token li
     const int colw = n0 + wave * WAVE_COLS;
@@ -424,7 +442,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void ffn_tiled_kernel(
         const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
         e = ent.x;
         const int local = L - ent.y * n_nt;
-        mt = local % ent.z;
+        mt = ent.w + local % ent.z;
         nt = local / ent.z;
     }
     const int sp = nt % nsp;      // column tile nt / nsp, K split nt % nsp
