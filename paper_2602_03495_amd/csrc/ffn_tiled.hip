@@ -401,7 +401,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void ffn_tiled_kernel(
     const uint16_t *__restrict__ wa, const uint16_t *__restrict__ wb,   // MODE 0: packed w1, w3; MODE 1: packed w2, unused
     const int32_t *__restrict__ sched, const uint8_t *__restrict__ mask,   // DIRECT: mask instead of a schedule
     uint16_t *__restrict__ out,                                            // MODE 0: act [R,I]; MODE 1: y [R,d]
-    int nsp_max, float *__restrict__ part, int R)   // MODE 1: up to nsp_max K splits per tile, partial sums in part [nsp,R,d] fp32
+    int nsp_max, float *__restrict__ part, int R,   // MODE 1: up to nsp_max K splits per tile, partial sums in part [nsp,R,d] fp32
+    int group)                                      // column tiles that alternate inside the item order of an expert (1: column tile major)
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][TM * 32];   // [buffer][k32 half][128 tokens x 32 k]
     // The up projection with its widest tile (NF = 4: 256 inner columns) can run its items with half that width instead:
@@ -442,8 +443,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void ffn_tiled_kernel(
         const int4 ent = reinterpret_cast<const int4 *>(sched + 4)[L / n_nt];
         e = ent.x;
         const int local = L - ent.y * n_nt;
-        mt = ent.w + local % ent.z;
-        nt = local / ent.z;
+        // Item order inside an expert: groups of `group` column tiles; inside a group the token tiles in turn, each with
+        // the group's column tiles side by side.  Blocks that follow each other in the list start close in time, so the
+        // blocks that share a token tile (same mt) and those that share a weight tile (same nt) both stay near each other.
+        const int per_group = group * ent.z;
+        const int g0 = local / per_group, within = local - g0 * per_group;
+        const int gsz = min(group, n_nt - g0 * group);         // the last group may hold fewer column tiles
+        mt = ent.w + within / gsz;
+        nt = g0 * group + within % gsz;
     }
     const int sp = nt % nsp;      // column tile nt / nsp, K split nt % nsp
     nt /= nsp;
@@ -526,6 +533,15 @@ __global__ __launch_bounds__(256) void tiled_finish_kernel(int d, int R, int N, 
     }
 }
 
+// measurement switch: how many column tiles alternate in the item order (see the kernel); 1 = column tile major
+static int tiled_item_group(int mode)
+{
+    static const int up = getenv("MOE_TILED_GROUP_UP") ? atoi(getenv("MOE_TILED_GROUP_UP")) : 1;
+    static const int dn = getenv("MOE_TILED_GROUP_DOWN") ? atoi(getenv("MOE_TILED_GROUP_DOWN")) : 1;
+    const int g = mode == 0 ? up : dn;
+    return g < 1 ? 1 : g;
+}
+
 template <int MODE, int NF, int NTT, bool DIRECT, int NSETS, bool FENCED, int WAVES>
 static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, const int32_t *perm, const int32_t *offsets,
                          const int32_t *counts, const uint16_t *wa, const uint16_t *wb, const int32_t *sched,
@@ -541,7 +557,7 @@ static void launch_tiled(const moe_shape *s, long max_mt, const uint16_t *x, con
     const long n_e = s->N < (long)s->T * s->k ? s->N : (long)s->T * s->k;   // DIRECT: experts that can be non-empty
     const dim3 grid((unsigned)((DIRECT ? n_e : max_mt) * n_nt));
     hipLaunchKernelGGL((ffn_tiled_kernel<MODE, NF, NTT, DIRECT, NSETS, FENCED, WAVES>), grid, dim3(WAVES * 64), 0, st, s->d, s->I, s->k,
-                       s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R);
+                       s->N, x, perm, offsets, counts, wa, wb, sched, mask, out, nsp_max, part, R, tiled_item_group(MODE));
 }
 
 // Weight fragments per wave (NF), 16-row token subtiles per tile (NTT) and weight register sets (NSETS).  An expert
