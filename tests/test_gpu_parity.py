@@ -465,3 +465,49 @@ def test_shared_experts_appended_to_the_routing_tables(gpu, name, T):
         # and against the separate-launch path of the same library (the shared term is rounded to bf16 once per block there)
         sep = L.forward(hd, dw, None if m is None else torch.from_numpy(m).cuda()).float().cpu().numpy()[keep]
         assert rel_err(sep, ref) <= OUT_TOL
+
+
+@pytest.mark.parametrize("name,T", [("mixtral_s", 300), ("deepseek_s", 700)])
+def test_prefill_graph_replays_equal_eager_runs(gpu, name, T):
+    # bench.py takes its prefill figure from HIP-graph replays too: a captured pass over a prefill-sized batch (tile
+    # schedule kernel, both tiled projections, shared experts, combine), replayed with new inputs and eager work in
+    # between, must reproduce the eager results bit for bit
+    B, Lm = gpu
+    cfg = SMALL[name]
+    print(f"prefill graph replay {name} T={T}", flush=True)
+    hl = make_host_layer(cfg)
+    dw = _upload(Lm, hl)
+    mask = torch.from_numpy(wl.mask_random(cfg, (3 * cfg.N) // 4)).cuda()
+    L = Lm.MoeLayer(cfg, T)
+    h_static = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=0)).clone()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        r = L.routing
+        return [x.clone() for x in (r.topk_idx, r.topk_w, r.counts, r.offsets, r.perm, r.inv_perm, L.out)]
+
+    inputs = [Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=d_)) for d_ in (1, 2, 1)]
+    eager = []
+    for x in inputs:
+        h_static.copy_(x)
+        L.forward(h_static, dw, mask)
+        eager.append(snapshot())
+    assert not torch.equal(eager[0][6], eager[1][6])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        L.forward(h_static, dw, mask)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        L.forward(h_static, dw, mask)
+    for i, x in enumerate(inputs):
+        h_static.copy_(x)
+        L.out.zero_()
+        L.y.zero_()
+        L.routing.counts.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        for a, b in zip(snapshot(), eager[i]):
+            assert torch.equal(a, b), (i, a.dtype, a.shape)
