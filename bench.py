@@ -31,7 +31,7 @@ PEAK_HBM = 8.0e12         # B/s, MI355X HBM3E peak
 # prints them: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for a
 # plain 1 GiB copy; the profile they come from is named beside them in the JSON line.
 TRAFFIC_SOURCE = "stored counter value from profiles/bench_mixtral_kernel_stats_and_hbm_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), not measured in this run"
-TRAFFIC_PREFILL = {"up": 2.3619e9 + 87.3e6, "down": 1.3637e9 + 27.2e6}
+TRAFFIC_PREFILL = {"up": 2.4432e9 + 87.3e6, "down": 1.3995e9 + 27.2e6}
 TRAFFIC_DECODE_UP = {1: 470.0e6 + 0.1e6, 16: 1.1752e9 + 0.7e6}
 
 
