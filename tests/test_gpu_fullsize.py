@@ -60,6 +60,7 @@ def config_mask(cfg, hl):
 
 
 CASES = [("mixtral", 2048), ("mixtral", 1), ("mixtral", 16), ("mixtral", 64), ("mixtral", 256),   # 64, 256: mid-sized batches
+         ("mixtral", 8192), ("mixtral", 16384),                                                                    # 16384 and 32768 routed rows: the tile tables of the larger survey batches
          ("deepseek", 2048), ("deepseek", 16), ("qwen15", 4096), ("qwen15", 1), ("qwen3", 16), ("qwen3", 128), ("qwen3", 2048)]
 
 
