@@ -260,6 +260,18 @@ int moe_append_shared(const moe_shape *s, int n_shared, const void *h, const voi
                       int32_t *x_perm, int32_t *x_inv_perm, void *stream);
 
 /*
+ * moe_route followed by moe_append_shared in one call, with the results of the two calls made one after the other
+ * (same arguments, same outputs, bit for bit: the routed tables AND the tables of the wider layer).  At decode sizes
+ * (T <= 16 and T*k <= 128) the block that selects the experts writes both sets of tables, so the step has one launch
+ * fewer; larger batches run the two calls in sequence.  Arguments as for the two calls (h is always read: it feeds the
+ * gate); workspace as for moe_route (may be NULL).  Errors: the union of the two calls' checks.
+ */
+int moe_route_shared(const moe_shape *s, int n_shared, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                     const void *w_sg, int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                     int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts, int32_t *x_offsets,
+                     int32_t *x_perm, int32_t *x_inv_perm, void *workspace, void *stream);
+
+/*
  * Calibration of res_vec (Section "Residual-Based Prefetching", the res_vec equation): the mean, over the tokens
  * of a calibration set, of the difference between a token's input feature at the next MoE layer and at this one.
  *

@@ -20,7 +20,7 @@ EXPORTS = ["moe_strerror", "moe_workspace_bytes", "moe_route", "moe_predict_work
            "moe_expert_ffn_stage", "moe_combine", "moe_dense_route", "moe_shared_gate", "moe_pack_weights",
            "moe_expert_times", "moe_greedy_assign", "moe_cache_step", "moe_res_vec_workspace_bytes",
            "moe_res_vec_accumulate", "moe_res_vec_finish", "moe_route_predict", "moe_append_shared",
-           "moe_expert_ffn_static", "moe_static_scratch_bytes", "moe_debug_set_trace"]
+           "moe_expert_ffn_static", "moe_static_scratch_bytes", "moe_debug_set_trace", "moe_route_shared"]
 
 
 class MoeShape(C.Structure):
@@ -319,4 +319,18 @@ def moe_append_shared(s: MoeShape, n_shared: int, h, w_sg, r: Routing, out: Rout
                                           _ptr(out.topk_idx, i32), _ptr(out.topk_w, torch.float32), _ptr(out.counts, i32),
                                           _ptr(out.offsets, i32), _ptr(out.perm, i32), _ptr(out.inv_perm, i32), _stream())
     _check(rc, "moe_append_shared")
+    return out
+
+
+def moe_route_shared(s: MoeShape, n_shared: int, h, gate_w, gate_bias, norm_mode: int, w_sg, r: Routing, out: Routing,
+                     ws: Optional[torch.Tensor]) -> Routing:
+    """moe_route + moe_append_shared in one call (one launch fewer at decode sizes); fills r and out, returns out."""
+    i32 = torch.int32
+    rc = load_library().moe_route_shared(C.byref(s), C.c_int(n_shared), _ptr(h, torch.bfloat16), _ptr(gate_w, torch.bfloat16),
+                                         _ptr(gate_bias, torch.float32), C.c_int(norm_mode), _ptr(w_sg, torch.bfloat16),
+                                         _ptr(r.topk_idx, i32), _ptr(r.topk_w, torch.float32), _ptr(r.counts, i32),
+                                         _ptr(r.offsets, i32), _ptr(r.perm, i32), _ptr(r.inv_perm, i32),
+                                         _ptr(out.topk_idx, i32), _ptr(out.topk_w, torch.float32), _ptr(out.counts, i32),
+                                         _ptr(out.offsets, i32), _ptr(out.perm, i32), _ptr(out.inv_perm, i32), _ws_ptr(ws), _stream())
+    _check(rc, "moe_route_shared")
     return out

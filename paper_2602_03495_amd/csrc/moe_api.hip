@@ -12,6 +12,9 @@ int moe_shared_gate_impl(const moe_shape *, const void *, const void *, float *,
 int moe_append_shared_impl(const moe_shape *, int, const void *, const void *, const int32_t *, const float *, const int32_t *,
                            const int32_t *, const int32_t *, const int32_t *, int32_t *, float *, int32_t *, int32_t *, int32_t *,
                            int32_t *, hipStream_t);
+int moe_route_shared_impl(const moe_shape *, int, const void *, const void *, const float *, int, const void *, int32_t *, float *,
+                          int32_t *, int32_t *, int32_t *, int32_t *, int32_t *, float *, int32_t *, int32_t *, int32_t *, int32_t *,
+                          void *, hipStream_t);
 int moe_ffn_tiled_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
                        const void *, const void *, const uint8_t *, void *, void *, int, hipStream_t);
 int moe_ffn_skinny_impl(const moe_shape *, const void *, const int32_t *, const int32_t *, const int32_t *, const void *,
@@ -214,6 +217,26 @@ int moe_append_shared(const moe_shape *s, int n_shared, const void *h, const voi
     if (w_sg != nullptr && (h == nullptr || !aligned16(h) || !aligned16(w_sg))) return MOE_EINVAL;
     return moe_append_shared_impl(s, n_shared, h, w_sg, topk_idx, topk_w, counts, offsets, perm, inv_perm, x_topk_idx, x_topk_w,
                                   x_counts, x_offsets, x_perm, x_inv_perm, (hipStream_t)stream);
+}
+
+int moe_route_shared(const moe_shape *s, int n_shared, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                     const void *w_sg, int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                     int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts, int32_t *x_offsets,
+                     int32_t *x_perm, int32_t *x_inv_perm, void *workspace, void *stream)
+{
+    int rc = check_shape(s, false);
+    if (rc != MOE_OK) return rc;
+    if (!h || !gate_w || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    if (!aligned16(h) || !aligned16(gate_w)) return MOE_EINVAL;
+    if (norm_mode != MOE_NORM_NONE && norm_mode != MOE_NORM_RENORM) return MOE_EINVAL;
+    if (workspace != nullptr && ((uintptr_t)workspace & 255u) != 0) return MOE_EWORKSPACE;
+    if (workspace != nullptr && (s->I < 128 || s->I % 128 != 0)) return MOE_EINVAL;
+    if (n_shared < 1 || s->N + n_shared > MOE_MAX_EXPERTS || s->k + n_shared > MOE_MAX_TOPK) return MOE_EINVAL;
+    if ((long long)s->T * (s->k + n_shared) >= (1ll << 31)) return MOE_EINVAL;
+    if (!x_topk_idx || !x_topk_w || !x_counts || !x_offsets || !x_perm || !x_inv_perm) return MOE_EINVAL;
+    if (w_sg != nullptr && !aligned16(w_sg)) return MOE_EINVAL;
+    return moe_route_shared_impl(s, n_shared, h, gate_w, gate_bias, norm_mode, w_sg, topk_idx, topk_w, counts, offsets, perm, inv_perm,
+                                 x_topk_idx, x_topk_w, x_counts, x_offsets, x_perm, x_inv_perm, workspace, (hipStream_t)stream);
 }
 
 int moe_route_predict(const moe_shape *s, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,

@@ -101,15 +101,45 @@ __device__ __forceinline__ void select_token(float v0, float v1, int N, int k, i
     }
 }
 
+// Weight of a sigmoid-gated shared expert for one token, by one wavefront: c = 1 / (1 + exp(-(x . w_sg))).  One
+// definition for every caller, so the value does not depend on which kernel evaluates it.
+__device__ __forceinline__ float sigmoid_gate_of(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w_sg, int d, int lane)
+{
+    float acc = 0.f;
+    for (int j = lane * 8; j < d; j += 512) {
+        uint4 a = *reinterpret_cast<const uint4 *>(x + j);
+        uint4 b = *reinterpret_cast<const uint4 *>(w_sg + j);
+        acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+        acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+        acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+        acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+    }
+    acc = wave_sum(acc);
+    return 1.0f / (1.0f + expf(-acc));
+}
+
+// Outputs of the wider layer (N + S experts, k + S slots per token: the S always-on shared experts appended, as
+// append_shared_kernel writes them) that the selecting block of a decode-sized batch can write itself; S = 0: none.
+struct shared_tail {
+    int S, d;
+    const uint16_t *h, *w_sg;          // w_sg null: weight 1
+    int32_t *x_idx;
+    float *x_w;
+    int32_t *x_counts, *x_offsets, *x_perm, *x_inv;
+};
+
 // Histogram, scan and stable permutation of a decode-sized batch (T <= 16, R = T*k <= 128 selections in sel_idx, LDS)
 // by one block.  A token selects an expert at most once, so the rows of expert e are one per selecting token, in
 // token order: a 16-bit token mask per expert gives the workload (its popcount) and the rank of a row within its
 // expert (the popcount below the token's bit) without any serial pass.  With perm == nullptr (a prediction) the
 // workloads and the p largest of them are written instead.  Every thread of the block must call it.
+// With X.S > 0 (routing only) the tables of the layer with its shared experts appended follow from the same LDS state:
+// sel_w holds the combine weights of the R selections, cs is room for T floats.
 __device__ __forceinline__ void decode_tables(const int *sel_idx, unsigned *tokmask, int *off_s, int T, int N, int k,
                                               int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
                                               int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-                                              int32_t *__restrict__ top, int p)
+                                              int32_t *__restrict__ top, int p, const float *sel_w, float *cs,
+                                              const shared_tail &X)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int R = T * k;
@@ -148,11 +178,40 @@ __device__ __forceinline__ void decode_tables(const int *sel_idx, unsigned *tokm
     }
     if (perm == nullptr) return;
     __syncthreads();
+    int pos = 0;
     if ((int)threadIdx.x < R) {
-        const int pos = off_s[my_e] + __popc(tokmask[my_e] & ((1u << my_t) - 1u));
+        pos = off_s[my_e] + __popc(tokmask[my_e] & ((1u << my_t) - 1u));
         perm[pos] = threadIdx.x;
         inv_perm[threadIdx.x] = pos;
     }
+    if (X.S <= 0) return;
+    // ---- the same layer as N + S experts with k + S slots per token (what append_shared_kernel derives from the tables)
+    const int S = X.S, kx = k + S, tid = threadIdx.x, nthreads = blockDim.x;
+    for (int t = wave; t < T; t += nthreads >> 6) {
+        const float c = X.w_sg != nullptr ? sigmoid_gate_of(X.h + (size_t)t * X.d, X.w_sg, X.d, lane) : 1.0f;
+        if (lane == 0) cs[t] = c;
+    }
+    __syncthreads();
+    if (tid < R) {                                             // routed slots keep their order; slot ids move to the wider stride
+        const int o = my_t * kx + (tid - my_t * k);
+        X.x_idx[o] = my_e;
+        X.x_w[o] = sel_w[tid];
+        X.x_inv[o] = pos;
+        X.x_perm[pos] = tid + my_t * S;
+    }
+    for (int i = tid; i < T * S; i += nthreads) {              // shared expert j takes slot k + j of every token
+        const int j = i / T, t = i - j * T;
+        const int o = t * kx + k + j, row = R + j * T + t;
+        X.x_idx[o] = N + j;
+        X.x_w[o] = cs[t];
+        X.x_inv[o] = row;
+        X.x_perm[row] = o;
+    }
+    for (int e = tid; e < N + S; e += nthreads) {
+        X.x_counts[e] = e < N ? __popc(tokmask[e]) : T;
+        X.x_offsets[e] = e < N ? off_s[e] : R + (e - N) * T;
+    }
+    if (tid == 0) X.x_offsets[N + S] = R + S * T;
 }
 
 // One gate to evaluate: the layer's own (routing) or the next layer's (prediction).  A launch carries two jobs and
@@ -170,6 +229,7 @@ struct gate_job {
     float *logits_out;         // non-null: only compute the logits of experts 16*NT*blockIdx.y .. and store them [T,N]
     int32_t *top;              // with counts and without perm: the p largest workloads
     int p;
+    shared_tail x;             // x.S > 0 (with perm, decode-sized launches only): also write the tables with the shared experts appended
 };
 
 template <int NT>   // NT = ceil(N / 16) expert tiles
@@ -302,7 +362,10 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, 
         if (lane < k) {
             topk_idx[(size_t)t * k + lane] = my_idx;
             topk_w[(size_t)t * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
-            if (counts != nullptr) reinterpret_cast<int *>(&part[0][0][0])[tt * k + lane] = my_idx;   // keep for the tail below
+            if (counts != nullptr) {                                                                  // keep for the tail below
+                reinterpret_cast<int *>(&part[0][0][0])[tt * k + lane] = my_idx;
+                (&part[1][0][0])[tt * k + lane] = norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+            }
         }
     }
     if (counts == nullptr) return;
@@ -310,7 +373,8 @@ __global__ __launch_bounds__(ROUTE_THREADS) void gate_topk_kernel(int T, int d, 
     // ---- decode-sized batch (one block, T <= 16): histogram, scan and stable permutation right here ----------
     __shared__ unsigned tokmask[MOE_MAX_EXPERTS];
     __shared__ int off_s[MOE_MAX_EXPERTS];
-    decode_tables(reinterpret_cast<const int *>(&part[0][0][0]), tokmask, off_s, T, N, k, counts, offsets, perm, inv_perm, top, p);
+    decode_tables(reinterpret_cast<const int *>(&part[0][0][0]), tokmask, off_s, T, N, k, counts, offsets, perm, inv_perm, top, p,
+                  &part[1][0][0], &part[2][0][0], J.x);
 }
 
 // Selection for a decode-sized batch from stored logits [T, N] (bias already added): one wavefront per token, then
@@ -320,6 +384,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_decode_kernel(int T, in
 {
     const gate_job &J = blockIdx.z == 0 ? job0 : job1;
     __shared__ int sel_idx[ROUTE_TOKENS * MOE_MAX_TOPK];
+    __shared__ float sel_w[ROUTE_TOKENS * MOE_MAX_TOPK], cs[ROUTE_TOKENS];
     __shared__ unsigned tokmask[MOE_MAX_EXPERTS];
     __shared__ int off_s[MOE_MAX_EXPERTS];
     const int lane = threadIdx.x & 63, t = threadIdx.x >> 6;
@@ -333,12 +398,14 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_decode_kernel(int T, in
         select_token(v0, v1, N, k, lane, my_idx, my_p, sel);
         if (lane < k) {
             J.topk_idx[(size_t)t * k + lane] = my_idx;
-            J.topk_w[(size_t)t * k + lane] = J.norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+            const float wgt = J.norm_mode == MOE_NORM_RENORM ? my_p / sel : my_p;
+            J.topk_w[(size_t)t * k + lane] = wgt;
             sel_idx[t * k + lane] = my_idx;
+            sel_w[t * k + lane] = wgt;
         }
     }
     __syncthreads();
-    decode_tables(sel_idx, tokmask, off_s, T, N, k, J.counts, J.offsets, J.perm, J.inv_perm, J.top, J.p);
+    decode_tables(sel_idx, tokmask, off_s, T, N, k, J.counts, J.offsets, J.perm, J.inv_perm, J.top, J.p, sel_w, cs, J.x);
 }
 
 // Selection from stored logits [T, N] for any batch size: one wavefront per token, 16 tokens per block.
@@ -502,18 +569,8 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(int T, int d, const ui
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
-    const uint16_t *x = h + (size_t)t * d;
-    float acc = 0.f;
-    for (int j = lane * 8; j < d; j += 512) {
-        uint4 a = *reinterpret_cast<const uint4 *>(x + j);
-        uint4 b = *reinterpret_cast<const uint4 *>(w_sg + j);
-        acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-        acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-        acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-        acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) scale[t] = 1.0f / (1.0f + expf(-acc));
+    const float c = sigmoid_gate_of(h + (size_t)t * d, w_sg, d, lane);
+    if (lane == 0) scale[t] = c;
 }
 
 // Tables of the layer seen as N + S experts with k + S slots per token: the S always-on experts become experts
@@ -532,20 +589,7 @@ __global__ __launch_bounds__(256) void append_shared_kernel(
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t < T) {
         float c = 1.0f;
-        if (w_sg != nullptr) {
-            const uint16_t *x = h + (size_t)t * d;
-            float acc = 0.f;
-            for (int j = lane * 8; j < d; j += 512) {
-                uint4 a = *reinterpret_cast<const uint4 *>(x + j);
-                uint4 b = *reinterpret_cast<const uint4 *>(w_sg + j);
-                acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-                acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-                acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-                acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
-            }
-            acc = wave_sum(acc);
-            c = 1.0f / (1.0f + expf(-acc));
-        }
+        if (w_sg != nullptr) c = sigmoid_gate_of(h + (size_t)t * d, w_sg, d, lane);
         if (lane < kx) {
             const int o = t * kx + lane;
             if (lane < k) {
@@ -752,6 +796,37 @@ int moe_dense_route_impl(const moe_shape *s, int32_t *counts, int32_t *offsets, 
     hipLaunchKernelGGL(dense_route_kernel, dim3((n + 255) / 256), dim3(256), 0, st, s->T, s->N, counts, offsets, perm);
     MOE_CHECK_LAUNCH();
     return MOE_OK;
+}
+
+int moe_append_shared_impl(const moe_shape *, int, const void *, const void *, const int32_t *, const float *, const int32_t *,
+                           const int32_t *, const int32_t *, const int32_t *, int32_t *, float *, int32_t *, int32_t *, int32_t *,
+                           int32_t *, hipStream_t);
+
+// moe_route followed by moe_append_shared; at decode sizes the selecting block writes both sets of tables
+int moe_route_shared_impl(const moe_shape *s, int n_shared, const void *h, const void *gate_w, const float *gate_bias, int norm_mode,
+                          const void *w_sg, int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                          int32_t *inv_perm, int32_t *x_topk_idx, float *x_topk_w, int32_t *x_counts, int32_t *x_offsets,
+                          int32_t *x_perm, int32_t *x_inv_perm, void *workspace, hipStream_t st)
+{
+    if (!single_block_routing(s)) {
+        int rc = moe_route_impl(s, h, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace, st);
+        if (rc != MOE_OK) return rc;
+        return moe_append_shared_impl(s, n_shared, h, w_sg, topk_idx, topk_w, counts, offsets, perm, inv_perm, x_topk_idx, x_topk_w,
+                                      x_counts, x_offsets, x_perm, x_inv_perm, st);
+    }
+    gate_job j = route_job(s, gate_w, gate_bias, norm_mode, topk_idx, topk_w, counts, offsets, perm, inv_perm);
+    j.x.S = n_shared;
+    j.x.d = s->d;
+    j.x.h = (const uint16_t *)h;
+    j.x.w_sg = (const uint16_t *)w_sg;
+    j.x.x_idx = x_topk_idx;
+    j.x.x_w = x_topk_w;
+    j.x.x_counts = x_counts;
+    j.x.x_offsets = x_offsets;
+    j.x.x_perm = x_perm;
+    j.x.x_inv = x_inv_perm;
+    float *wl[1] = {route_logits_scratch(s, workspace, 0)};
+    return launch_gate_topk(s, h, st, 1, &j, wl);
 }
 
 int moe_shared_gate_impl(const moe_shape *s, const void *h, const void *w_sg, float *scale, hipStream_t st)

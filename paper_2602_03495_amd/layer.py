@@ -145,9 +145,9 @@ class MoeLayer:
         one expert FFN over routed and shared experts -> combine.  xmask: merged_mask(mask), or None for all on."""
         if not self.n_merged or w.xw1 is None:
             raise B.MoeError("this layer has no shared experts that split into experts of the routed inner size")
-        self.route(h, w, bias)
-        x = B.moe_append_shared(self.shape, self.n_merged, h, w.w_sg if self.shared_scale is not None else None,
-                                self.routing, self.xrouting)
+        b = w.gate_bias if bias is None else bias
+        x = B.moe_route_shared(self.shape, self.n_merged, h, w.gate_w, b, self.cfg.norm_mode,
+                               w.w_sg if self.shared_scale is not None else None, self.routing, self.xrouting, self.ws)
         B.moe_expert_ffn(self.xshape, h, x.perm, x.offsets, x.counts, w.xw1, w.xw3, w.xw2, xmask, self.xy, self.xws)
         return B.moe_combine(self.xshape, self.xy, x.topk_idx, x.topk_w, x.inv_perm, xmask, None, 0, None, self.out)
 

@@ -158,3 +158,18 @@ def test_expert_ffn_refuses_weights_not_declared_as_packed(lib):
     # the tag is read by the expert-FFN calls only
     n = C.c_size_t(0)
     assert lib.moe_workspace_bytes(C.byref(Shape(16, 256, 8, 2, 512, 0, 0)), C.byref(n)) == MOE_OK
+
+
+def test_route_shared_rejects_bad_arguments_before_launching(lib):
+    s = Shape(16, 256, 8, 2, 512, 0, 1)
+    p, z = C.c_void_p(0x1000), C.c_void_p(0)
+    call = lambda n_sh, h, wsg, *tables: lib.moe_route_shared(C.byref(s), n_sh, h, p, z, 1, wsg, *tables, p, z)
+    ok = (p,) * 12
+    assert call(0, p, z, *ok) == MOE_EINVAL                                        # no shared expert
+    assert call(7, p, z, *ok) == MOE_EINVAL                                        # k + n_shared > 8 slots
+    assert call(2, z, z, *ok) == MOE_EINVAL                                        # h feeds the gate: required
+    assert call(2, p, C.c_void_p(0x1004), *ok) == MOE_EINVAL                       # gate vector misaligned
+    for i in range(12):                                                            # every table pointer is required
+        assert call(2, p, z, *(ok[:i] + (z,) + ok[i + 1:])) == MOE_EINVAL
+    assert lib.moe_route_shared(C.byref(s), 2, p, p, z, 5, z, *ok, p, z) == MOE_EINVAL                  # bad norm mode
+    assert lib.moe_route_shared(C.byref(s), 2, p, p, z, 1, z, *ok, C.c_void_p(0x1010), z) == MOE_EWORKSPACE

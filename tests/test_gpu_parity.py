@@ -511,3 +511,37 @@ def test_prefill_graph_replays_equal_eager_runs(gpu, name, T):
         g.replay()
         for a, b in zip(snapshot(), eager[i]):
             assert torch.equal(a, b), (i, a.dtype, a.shape)
+
+
+@pytest.mark.parametrize("name,T", [("deepseek_m", 1), ("deepseek_m", 16), ("deepseek_m", 9), ("qwen15_m", 1), ("qwen15_m", 16),
+                                    ("deepseek_m", 333), ("qwen15_m", 40)])
+def test_route_shared_equals_the_two_calls(gpu, name, T):
+    # one call that routes and appends the shared experts' slots must give exactly what moe_route followed by
+    # moe_append_shared gives (both checked against the oracle elsewhere): at decode sizes, where the selecting block
+    # writes both sets of tables (8 experts: in the gate kernel itself; more: in the selection kernel), and beyond
+    B, Lm = gpu
+    cfg = MERGED[name]
+    if name == "deepseek_m" and T == 9:
+        cfg = wl.scaled(cfg, N=8, k=2)                    # at most 16 experts: gate, selection and tables in one kernel
+    print(f"route_shared {cfg.name} N={cfg.N} T={T}", flush=True)
+    S = cfg.n_shared * (cfg.I_shared // cfg.I)
+    h = Lm.to_device_bf16(wl.hidden_states(cfg, T, draw=7))
+    W, b = Lm.to_device_bf16(wl.gate_weights(cfg)), torch.from_numpy(wl.gate_bias(cfg)).cuda()
+    w_sg = Lm.to_device_bf16(wl.shared_expert_weights(cfg)[3]) if cfg.shared_gate == "sigmoid" else None
+    s = B.shape(T, cfg.d, cfg.N, cfg.k, cfg.I)
+    sx = B.shape(T, cfg.d, cfg.N + S, cfg.k + S, cfg.I)
+    for use_ws in (True, False):
+        ws = B.alloc_workspace(s) if use_ws else None
+        ra, rb, xa, xb = B.alloc_routing(s), B.alloc_routing(s), B.alloc_routing(sx), B.alloc_routing(sx)
+        for r in (ra, rb, xa, xb):
+            for f in ("topk_idx", "counts", "offsets", "perm", "inv_perm"):
+                getattr(r, f).fill_(-5)
+            r.topk_w.fill_(-5.0)
+        B.moe_route(s, h, W, b, cfg.norm_mode, ra, ws)
+        B.moe_append_shared(s, S, h, w_sg, ra, xa)
+        B.moe_route_shared(s, S, h, W, b, cfg.norm_mode, w_sg, rb, xb, ws)
+        torch.cuda.synchronize()
+        for f in ("topk_idx", "topk_w", "counts", "offsets", "perm", "inv_perm"):
+            assert torch.equal(getattr(ra, f), getattr(rb, f)), ("routed", f)
+            assert torch.equal(getattr(xa, f), getattr(xb, f)), ("wider", f)
+        assert int(xb.counts.sum()) == T * (cfg.k + S) and int(xb.counts[cfg.N:].min()) == T
